@@ -1,0 +1,672 @@
+// Causal vertical-slash sparse attention and dense causal attention for gfx950.
+//
+// One workgroup (4 wavefronts) owns a query tile of one KV head: 8 "row blocks" of 32 query rows,
+// arranged as hc query heads of the KV group times 8/hc consecutive 32-row sub-blocks.  Each
+// wavefront owns two row blocks (two heads on the same rows when hc >= 2) so that every K / V
+// fragment read from LDS feeds two MFMAs.
+//
+// Scores are computed transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: a lane then holds
+// 16 keys of ONE query, which makes the row maximum a 16-way in-lane reduction plus one
+// half-wave swap, and makes the S^T accumulator directly usable as the B operand (P^T) of the
+// second product O^T = V^T P^T.  V^T fragments come from LDS through the transposing read.
+//
+// Sparse path (Sec. "Fused attention kernel implementation" of the paper: indices read per query
+// tile, merged on the fly, keys fetched on demand).  The selected offsets and columns of a head are
+// expanded once into bitmaps.  Per query tile the workgroup
+//   1. marks the 32-key blocks that any selected diagonal crosses (they form the merged
+//      contiguous key ranges of the slash part),
+//   2. walks the sorted column list and keeps the columns that are causal for the tile and do NOT
+//      fall inside a marked block (those are covered by the block's own mask): the deduplicated
+//      gather list,
+//   3. streams marked blocks (coalesced rows) and gathered columns (row gathers) through LDS and
+//      runs online-softmax attention on them.  The exact element mask
+//          live(i, j) = j <= i and ( offset i-j selected  or  column j selected )
+//      is a 63-bit window of the offset bitmap per 32x32 tile (tile-uniform, held in SGPRs) plus
+//      a 32-bit column word; interior tiles whose window is all ones skip the mask.
+#include <hip/hip_runtime.h>
+#include <limits.h>
+#include <math.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+#include "vs_common.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4t __attribute__((__vector_size__(4 * sizeof(__bf16))));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kD = 128;
+constexpr int kThreads = 256;
+constexpr int kRowBytes = 288;                 // 256 B of data + 32 B pad: conflict-free b128 and transposing reads
+constexpr int kStageKeys = 64;                 // two 32-key tiles per LDS stage
+constexpr int kTileBytes = 32 * kRowBytes;     // one 32-key tile of K or V
+constexpr int kStageBytes = 2 * 2 * kTileBytes;  // K and V, two tiles
+constexpr int kListCap = 4096;                 // entries of the per-round tile / gather list
+constexpr int kTbitWords = 1024;               // touched-block bits for up to 32768 key blocks (n <= 2^20)
+constexpr size_t kSmemBytes = 2 * kStageBytes + kListCap * 4 + kTbitWords * 4 + 64;
+constexpr uint64_t kAll63 = 0x7fffffffffffffffull;
+constexpr float kRescaleThreshold = 8.0f;      // log2 units: stale maxima up to 2^8 are tolerated
+
+struct AttnParams {
+    const uint16_t* q;
+    const uint16_t* k;
+    const uint16_t* v;
+    uint16_t* o;
+    float* lse;
+    int q_heads, kv_heads, group, hc, n, tiles, index_per_q;
+    float scale, c;                 // c = scale * log2(e)
+    const int32_t* idx_v;
+    const int32_t* cnt_v;
+    int cap_v;
+    const uint32_t* sbit;           // per index head: bit (o + 64) set iff offset o selected
+    const uint32_t* vbit;           // per index head: bit j set iff column j selected
+    const uint32_t* t32;            // per index head: bit t set iff an offset in [32t-31, 32t+31] is selected
+    int sw, vw, tw;                 // words per head of the three bitmaps
+    unsigned long long* tile_counter;
+};
+
+__device__ __forceinline__ uint64_t window64(const uint32_t* __restrict__ bm, int bitpos) {
+    const int w = bitpos >> 5, sh = bitpos & 31;
+    const uint32_t a = bm[w], b = bm[w + 1], c = bm[w + 2];
+    uint64_t r = ((static_cast<uint64_t>(b) << 32) | a) >> sh;
+    if (sh) r |= static_cast<uint64_t>(c) << (64 - sh);
+    return r;
+}
+
+__device__ __forceinline__ float half_swap_max(float x) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+__device__ __forceinline__ float half_swap_sum(float x) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Ordered append of the flagged threads' values to list[base...]; returns the new length.
+__device__ __forceinline__ int wg_append(bool flag, int value, int* list, int base, int* wtot) {
+    const uint64_t bal = __ballot(flag);
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int pre = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) wtot[w] = __popcll(bal);
+    __syncthreads();
+    int off = base, tot = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = wtot[i];
+        if (i < w) off += c;
+        tot += c;
+    }
+    if (flag) list[off + pre] = value;
+    __syncthreads();
+    return base + tot;
+}
+
+template <bool DENSE>
+__global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams p) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char* const kvbuf = smem;
+    int* const list = reinterpret_cast<int*>(smem + 2 * kStageBytes);
+    uint32_t* const tbits = reinterpret_cast<uint32_t*>(smem + 2 * kStageBytes + kListCap * 4);
+    int* const wtot = reinterpret_cast<int*>(smem + 2 * kStageBytes + kListCap * 4 + kTbitWords * 4);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int qi = lane & 31, hh = lane >> 5;
+    const float NEG_INF = -INFINITY;
+
+    // ---- which tile ----
+    const int bid = blockIdx.x;
+    const int g = bid % p.kv_heads;
+    const int rest = bid / p.kv_heads;
+    const int hchunks = p.group / p.hc;
+    const int hchunk = rest % hchunks;
+    const int tile = p.tiles - 1 - rest / hchunks;          // longest tiles first
+    const int BQ = 256 / p.hc;
+    const int nsub = BQ >> 5;
+    const int i0 = tile * BQ;
+    const int n = p.n;
+    const int i_last = min(i0 + BQ, n) - 1;
+
+    int slot_head[2], slot_i0[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const int rb = 2 * wave + s;
+        slot_head[s] = g * p.group + hchunk * p.hc + rb % p.hc;
+        slot_i0[s] = i0 + 32 * (rb / p.hc);
+    }
+    const int ih = p.index_per_q ? slot_head[0] : g;
+    const uint32_t* __restrict__ sbit = DENSE ? nullptr : p.sbit + static_cast<size_t>(ih) * p.sw;
+    const uint32_t* __restrict__ vbit = DENSE ? nullptr : p.vbit + static_cast<size_t>(ih) * p.vw;
+    const uint32_t* __restrict__ t32 = DENSE ? nullptr : p.t32 + static_cast<size_t>(ih) * p.tw;
+
+    const uint16_t* __restrict__ kbase = p.k + static_cast<size_t>(g) * n * kD;
+    const uint16_t* __restrict__ vbase = p.v + static_cast<size_t>(g) * n * kD;
+
+    // ---- Q fragments: B operand of S^T = K Q^T; lane holds query qi, d = 16 kk + 8 hh .. +7 ----
+    bf16x8 qf[2][8];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const int row = slot_i0[s] + qi;
+        const uint16_t* src = p.q + (static_cast<size_t>(slot_head[s]) * n + min(row, n - 1)) * kD + 8 * hh;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            uint4 raw = make_uint4(0, 0, 0, 0);
+            if (row < n) raw = *reinterpret_cast<const uint4*>(src + 16 * kk);
+            qf[s][kk] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+
+    f32x16 oacc[2][4];
+    float m_run[2], l_run[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        m_run[s] = NEG_INF;
+        l_run[s] = 0.f;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[s][db][e] = 0.f;
+    }
+    unsigned int tiles_done = 0;
+
+    // ---- staging: thread loads chunk (tid & 15) of rows (tid >> 4) + 16 u, u = 0..3 ----
+    const int st_row = tid >> 4, st_chunk = tid & 15;
+    uint4 kreg[4], vreg[4];
+
+    // row_of(u): global key row for staged row st_row + 16 u, or -1
+    auto load_rows = [&](const int (&rows)[4]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            kreg[u] = make_uint4(0, 0, 0, 0);
+            vreg[u] = make_uint4(0, 0, 0, 0);
+            if (rows[u] >= 0) {
+                const size_t off = static_cast<size_t>(rows[u]) * kD + st_chunk * 8;
+                kreg[u] = *reinterpret_cast<const uint4*>(kbase + off);
+                vreg[u] = *reinterpret_cast<const uint4*>(vbase + off);
+            }
+        }
+    };
+    auto store_rows = [&](int buf) __attribute__((always_inline)) {
+        unsigned char* kb = kvbuf + buf * kStageBytes;
+        unsigned char* vb = kb + 2 * kTileBytes;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int off = (st_row + 16 * u) * kRowBytes + st_chunk * 16;
+            *reinterpret_cast<uint4*>(kb + off) = kreg[u];
+            *reinterpret_cast<uint4*>(vb + off) = vreg[u];
+        }
+    };
+
+    // ---- one 32-key tile against both row blocks of this wavefront ----
+    auto compute_tile = [&](const unsigned char* kt, const unsigned char* vt, const bool (&live)[2],
+                            const bool (&need)[2], const uint32_t (&mb)[2]) __attribute__((always_inline)) {
+        if (!live[0] && !live[1]) return;
+        bf16x8 kf[8];
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk)
+            kf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(kt + qi * kRowBytes + kk * 32 + hh * 16));
+        bf16x8 pb[2][2];
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            if (!live[s]) continue;
+            ++tiles_done;
+            f32x16 acc;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[s][kk], acc, 0, 0, 0);
+            if (need[s]) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int bit = 27 - 8 * (e >> 2) - (e & 3);
+                    if (!((mb[s] >> bit) & 1u)) acc[e] = NEG_INF;
+                }
+            }
+            float mx = acc[0];
+#pragma unroll
+            for (int e = 1; e < 16; ++e) mx = fmaxf(mx, acc[e]);
+            mx = half_swap_max(mx);
+            const float m_new = fmaxf(m_run[s], mx);
+            const bool grow = (m_new - m_run[s]) * p.c > kRescaleThreshold;   // false when both are -inf
+            if (__ballot(grow)) {
+                const float alpha = (m_new == NEG_INF) ? 1.f : __builtin_amdgcn_exp2f((m_run[s] - m_new) * p.c);
+#pragma unroll
+                for (int db = 0; db < 4; ++db)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) oacc[s][db][e] *= alpha;
+                l_run[s] *= alpha;
+                m_run[s] = m_new;
+            }
+            const float mc = (m_run[s] == NEG_INF) ? 0.f : m_run[s] * p.c;
+            float lsum = 0.f;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                acc[e] = __builtin_amdgcn_exp2f(fmaf(acc[e], p.c, -mc));
+                lsum += acc[e];
+            }
+            l_run[s] += lsum;
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) {
+                    f32x2 two = {acc[8 * t + e], acc[8 * t + e + 1]};
+                    bf16x2 r = __builtin_convertvector(two, bf16x2);
+                    pb[s][t][e] = r[0];
+                    pb[s][t][e + 1] = r[1];
+                }
+        }
+        // O^T += V^T P^T.  Transposing LDS read: within 16 lanes, lane i addresses row i/4, 4 columns at
+        // 4 (i%4); it receives column i of those 4 rows, i.e. 4 consecutive keys of one d.
+        const int li = lane & 15, dsel = (lane >> 4) & 1;
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const unsigned char* a0 = vt + (16 * t + 4 * hh + (li >> 2)) * kRowBytes + (32 * db + 16 * dsel + 4 * (li & 3)) * 2;
+                const unsigned char* a1 = a0 + 8 * kRowBytes;
+                typedef __attribute__((address_space(3))) bf16x4t* lds_ptr_t;
+                bf16x4t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr_t)(a0));
+                bf16x4t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr_t)(a1));
+                bf16x8 vf;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    vf[e] = lo[e];
+                    vf[4 + e] = hi[e];
+                }
+#pragma unroll
+                for (int s = 0; s < 2; ++s)
+                    if (live[s]) oacc[s][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[s][t], oacc[s][db], 0, 0, 0);
+            }
+        }
+    };
+
+    // ---- per-tile mask words ----
+    // contiguous block b (keys 32 b .. 32 b + 31)
+    auto block_masks = [&](int b, bool (&live)[2], bool (&need)[2], uint32_t (&mb)[2]) __attribute__((always_inline)) {
+        const int j0 = 32 * b;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int dlt = slot_i0[s] - j0;                 // offset of (row 0, key 0) of the 32x32 tile
+            live[s] = false;
+            need[s] = false;
+            mb[s] = 0;
+            if (dlt < -31 || slot_i0[s] >= n) continue;      // every key lies after every row / padding rows
+            const uint64_t cz = dlt >= 31 ? kAll63 : ((kAll63 << (31 - dlt)) & kAll63);   // offsets >= 0
+            uint64_t w;
+            uint32_t vw = 0;
+            if (DENSE) {
+                w = cz;
+            } else {
+                w = window64(sbit, dlt + 33) & kAll63;       // offsets dlt-31 .. dlt+31 at bits 0..62 (64-bit guard in front)
+                vw = vbit[b];
+            }
+            live[s] = (w | (vw ? cz : 0ull)) != 0ull;
+            need[s] = w != kAll63;
+            const int sh = 4 + qi - 4 * hh;
+            const uint32_t wl = static_cast<uint32_t>(w >> sh), cl = static_cast<uint32_t>(cz >> sh);
+            const uint32_t vl = __builtin_bitreverse32(vw) >> (4 - 4 * hh);
+            mb[s] = wl | (vl & cl);
+        }
+    };
+    // gathered tile: 32 columns at cols[0..31] (ascending, INT_MAX padding)
+    auto gather_masks = [&](const int* cols, bool (&live)[2], bool (&need)[2], uint32_t (&mb)[2]) __attribute__((always_inline)) {
+        const int cmin = cols[0], cmax = cols[31];
+        int c[16];
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            const int4 c4 = *reinterpret_cast<const int4*>(cols + 8 * a + 4 * hh);
+            c[4 * a] = c4.x; c[4 * a + 1] = c4.y; c[4 * a + 2] = c4.z; c[4 * a + 3] = c4.w;
+        }
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            live[s] = cmin <= slot_i0[s] + 31 && slot_i0[s] < n;
+            need[s] = cmax > slot_i0[s];
+            const int row = slot_i0[s] + qi;
+            uint32_t m = 0;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) m |= (c[e] <= row ? 1u : 0u) << (27 - 8 * (e >> 2) - (e & 3));
+            mb[s] = m;
+        }
+    };
+
+    // ---- software pipeline over the tiles of one phase ----
+    // GATHER == false: tile t is key block (DENSE ? t : list[t]);  GATHER == true: tile t is list[32 t .. 32 t + 31]
+    auto run_phase = [&](int ntiles, auto gather_tag) __attribute__((always_inline)) {
+        constexpr bool GATHER = decltype(gather_tag)::value;
+        const int nstages = (ntiles + 1) >> 1;
+        if (nstages == 0) return;
+        auto stage_rows = [&](int st, int (&rows)[4]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int r = st_row + 16 * u;
+                const int t = 2 * st + (r >> 5);
+                int row = -1;
+                if (t < ntiles) {
+                    if (GATHER) {
+                        const int col = list[32 * t + (r & 31)];
+                        row = col < n ? col : -1;
+                    } else {
+                        const int b = DENSE ? t : list[t];
+                        row = 32 * b + (r & 31);
+                        if (row >= n) row = -1;
+                    }
+                }
+                rows[u] = row;
+            }
+        };
+        int rows[4];
+        stage_rows(0, rows);
+        load_rows(rows);
+        store_rows(0);
+        __syncthreads();
+        for (int st = 0; st < nstages; ++st) {
+            const bool more = st + 1 < nstages;
+            if (more) {
+                stage_rows(st + 1, rows);
+                load_rows(rows);
+            }
+            const unsigned char* kb = kvbuf + (st & 1) * kStageBytes;
+            const unsigned char* vb = kb + 2 * kTileBytes;
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt) {
+                const int t = 2 * st + tt;
+                if (t < ntiles) {
+                    bool live[2], need[2];
+                    uint32_t mb[2];
+                    if (GATHER) {
+                        gather_masks(list + 32 * t, live, need, mb);
+                    } else {
+                        const int b = __builtin_amdgcn_readfirstlane(DENSE ? t : list[t]);
+                        block_masks(b, live, need, mb);
+                    }
+                    compute_tile(kb + tt * kTileBytes, vb + tt * kTileBytes, live, need, mb);
+                }
+            }
+            if (more) store_rows((st + 1) & 1);
+            __syncthreads();
+        }
+    };
+
+    // ---- phases ----
+    const int nblk = i_last / 32 + 1;                       // key blocks that hold causal keys for this tile
+    if (DENSE) {
+        run_phase(nblk, std::false_type{});
+    } else {
+        // 1. blocks crossed by a selected diagonal for any 32-row sub-block of the tile
+        const int qb0 = i0 >> 5;
+        for (int base = 0; base < nblk; base += kThreads) {
+            const int b = base + tid;
+            bool touched = false;
+            if (b < nblk) {
+                for (int r = 0; r < nsub; ++r) {
+                    const int dl = qb0 + r - b;
+                    if (dl >= 0) touched |= (t32[dl >> 5] >> (dl & 31)) & 1u;
+                }
+            }
+            const uint64_t bal = __ballot(touched);
+            if (lane == 0) {
+                tbits[(base >> 5) + 2 * wave] = static_cast<uint32_t>(bal);
+                tbits[(base >> 5) + 2 * wave + 1] = static_cast<uint32_t>(bal >> 32);
+            }
+        }
+        __syncthreads();
+        // 2. slash part: marked blocks, in rounds of kListCap candidate blocks
+        for (int rbase = 0; rbase < nblk; rbase += kListCap) {
+            int count = 0;
+            const int rend = min(nblk, rbase + kListCap);
+            for (int base = rbase; base < rend; base += kThreads) {
+                const int b = base + tid;
+                const bool flag = b < rend && ((tbits[b >> 5] >> (b & 31)) & 1u);
+                count = wg_append(flag, b, list, count, wtot);
+            }
+            run_phase(count, std::false_type{});
+        }
+        // 3. vertical part: causal columns outside the marked blocks, gathered row by row
+        const int32_t* __restrict__ iv = p.idx_v + static_cast<size_t>(ih) * p.cap_v;
+        int ncand;
+        {
+            int lo = 0, hi = min(p.cnt_v[ih], p.cap_v);     // first entry > i_last
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (iv[mid] <= i_last) lo = mid + 1; else hi = mid;
+            }
+            ncand = lo;
+        }
+        int cursor = 0;
+        while (cursor < ncand) {
+            int count = 0;
+            while (cursor < ncand && count + kThreads <= kListCap) {
+                const int t = cursor + tid;
+                const int col = t < ncand ? iv[t] : -1;
+                const bool flag = col >= 0 && !((tbits[col >> 10] >> ((col >> 5) & 31)) & 1u);
+                count = wg_append(flag, col, list, count, wtot);
+                cursor += kThreads;
+            }
+            const int padded = (count + 63) & ~63;
+            for (int t = count + tid; t < padded; t += kThreads) list[t] = INT_MAX;
+            __syncthreads();
+            run_phase((count + 31) >> 5, std::true_type{});
+        }
+    }
+
+    // ---- epilogue: O = O^T / l, bf16 store; lse = m * scale + ln(l) ----
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const float l_tot = half_swap_sum(l_run[s]);
+        const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+        const int row = slot_i0[s] + qi;
+        if (row < n) {
+            uint16_t* dst = p.o + (static_cast<size_t>(slot_head[s]) * n + row) * kD;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    f32x2 x01 = {oacc[s][db][4 * a] * inv, oacc[s][db][4 * a + 1] * inv};
+                    f32x2 x23 = {oacc[s][db][4 * a + 2] * inv, oacc[s][db][4 * a + 3] * inv};
+                    bf16x2 y01 = __builtin_convertvector(x01, bf16x2);
+                    bf16x2 y23 = __builtin_convertvector(x23, bf16x2);
+                    uint2 out;
+                    out.x = __builtin_bit_cast(uint32_t, y01);
+                    out.y = __builtin_bit_cast(uint32_t, y23);
+                    *reinterpret_cast<uint2*>(dst + 32 * db + 8 * a + 4 * hh) = out;
+                }
+            if (p.lse && hh == 0)
+                p.lse[static_cast<size_t>(slot_head[s]) * n + row] =
+                    l_tot > 0.f ? m_run[s] * p.scale + __logf(l_tot) : NEG_INF;
+        }
+    }
+    if (p.tile_counter && lane == 0 && tiles_done) atomicAdd(p.tile_counter, static_cast<unsigned long long>(tiles_done));
+}
+
+// ---- index lists -> bitmaps ----
+__global__ void fill_zero_kernel(uint32_t* p, size_t words) {
+    const size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < words) p[i] = 0u;
+}
+
+__global__ void set_bits_kernel(const int32_t* idx, const int32_t* cnt, int cap, int n, uint32_t* bits, int words_per_head,
+                                int bit_shift) {
+    const int ih = blockIdx.y;
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= min(cnt[ih], cap)) return;
+    const int e = idx[static_cast<size_t>(ih) * cap + t];
+    if (e < 0 || e >= n) return;
+    const int bit = e + bit_shift;
+    atomicOr(bits + static_cast<size_t>(ih) * words_per_head + (bit >> 5), 1u << (bit & 31));
+}
+
+// t32 bit t = any selected offset in [32 t - 31, 32 t + 31]
+__global__ void block_diag_kernel(const uint32_t* sbit, int sw, uint32_t* t32, int tw, int nbits) {
+    const int ih = blockIdx.y;
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    bool any = false;
+    if (t < nbits) any = (window64(sbit + static_cast<size_t>(ih) * sw, 32 * t + 33) & kAll63) != 0ull;
+    const uint64_t bal = __ballot(any);
+    if ((threadIdx.x & 63) == 0 && t < tw * 32) {
+        uint32_t* dst = t32 + static_cast<size_t>(ih) * tw + (t >> 5);
+        dst[0] = static_cast<uint32_t>(bal);
+        if ((t >> 5) + 1 < tw) dst[1] = static_cast<uint32_t>(bal >> 32);
+    }
+}
+
+struct SparseWs {
+    size_t counter_off, sbit_off, vbit_off, t32_off, total;
+    int sw, vw, tw;
+};
+
+SparseWs sparse_ws_layout(int index_heads, int64_t n) {
+    SparseWs w;
+    const int64_t nblk = (n + 31) / 32;
+    w.sw = static_cast<int>(vs::round_up(static_cast<size_t>(n + 64 + 160 + 31) / 32, 4));
+    w.vw = static_cast<int>(vs::round_up(static_cast<size_t>(nblk + 4), 4));
+    w.tw = static_cast<int>(vs::round_up(static_cast<size_t>(nblk + 1 + 31) / 32 + 2, 4));
+    w.counter_off = 0;
+    w.sbit_off = 256;
+    w.vbit_off = w.sbit_off + static_cast<size_t>(index_heads) * w.sw * 4;
+    w.t32_off = w.vbit_off + static_cast<size_t>(index_heads) * w.vw * 4;
+    w.total = vs::round_up(w.t32_off + static_cast<size_t>(index_heads) * w.tw * 4, 256);
+    return w;
+}
+
+int check_qkv(const void* q, const void* k, const void* v, int q_heads, int kv_heads, int64_t n, float scale, void* o) {
+    if (!q || !k || !v || !o) return VS_ERR_INVALID_ARG;
+    if (!vs::aligned16(q) || !vs::aligned16(k) || !vs::aligned16(v) || !vs::aligned16(o)) return VS_ERR_INVALID_ARG;
+    if (q_heads <= 0 || kv_heads <= 0 || n <= 0) return VS_ERR_INVALID_ARG;
+    if (!(scale > 0.f) || !isfinite(scale)) return VS_ERR_INVALID_ARG;
+    if (q_heads % kv_heads != 0) return VS_ERR_UNSUPPORTED;
+    if (n > VS_MAX_SEQ) return VS_ERR_UNSUPPORTED;
+    return VS_OK;
+}
+
+int heads_per_workgroup(int group, bool index_per_q) {
+    if (index_per_q) return 1;
+    if (group % 4 == 0) return 4;
+    if (group % 2 == 0) return 2;
+    return 1;
+}
+
+template <bool DENSE>
+int launch_attention(AttnParams& p, hipStream_t stream) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        VS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&vs_attention_kernel<DENSE>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kSmemBytes)));
+        attr_set = true;
+    }
+    const int BQ = 256 / p.hc;
+    p.tiles = (p.n + BQ - 1) / BQ;
+    const long long blocks = static_cast<long long>(p.kv_heads) * (p.group / p.hc) * p.tiles;
+    if (blocks > 0x7fffffffLL) return VS_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(vs_attention_kernel<DENSE>, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), kSmemBytes, stream, p);
+    VS_LAUNCH_CHECK();
+    return VS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t vs_sparse_prefill_workspace(int q_heads, int kv_heads, int index_heads, int64_t n) {
+    if (q_heads <= 0 || kv_heads <= 0 || n <= 0 || n > VS_MAX_SEQ) return 0;
+    if (index_heads != q_heads && index_heads != kv_heads) return 0;
+    return sparse_ws_layout(index_heads, n).total;
+}
+
+int vs_sparse_prefill(const void* q, const void* k, const void* v, int q_heads, int kv_heads, int64_t n, float scale,
+                      const int32_t* idx_v, const int32_t* cnt_v, int cap_v, const int32_t* idx_s, const int32_t* cnt_s,
+                      int cap_s, int index_heads, void* o_bf16, float* lse, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_qkv(q, k, v, q_heads, kv_heads, n, scale, o_bf16);
+    if (rc != VS_OK) return rc;
+    if (!idx_v || !cnt_v || !idx_s || !cnt_s || cap_v <= 0 || cap_s <= 0) return VS_ERR_INVALID_ARG;
+    if (index_heads != q_heads && index_heads != kv_heads) return VS_ERR_INVALID_ARG;
+    const SparseWs w = sparse_ws_layout(index_heads, n);
+    if (!ws || ws_bytes < w.total) return VS_ERR_WORKSPACE;
+    if (!vs::aligned16(ws)) return VS_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    unsigned char* base = static_cast<unsigned char*>(ws);
+    uint32_t* sbit = reinterpret_cast<uint32_t*>(base + w.sbit_off);
+    uint32_t* vbit = reinterpret_cast<uint32_t*>(base + w.vbit_off);
+    uint32_t* t32 = reinterpret_cast<uint32_t*>(base + w.t32_off);
+
+    const size_t words = w.total / 4;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(static_cast<unsigned>((words + 255) / 256)), dim3(256), 0, st,
+                       reinterpret_cast<uint32_t*>(base), words);
+    VS_LAUNCH_CHECK();
+    hipLaunchKernelGGL(set_bits_kernel, dim3((cap_s + 255) / 256, index_heads), dim3(256), 0, st, idx_s, cnt_s, cap_s,
+                       static_cast<int>(n), sbit, w.sw, 64);
+    VS_LAUNCH_CHECK();
+    hipLaunchKernelGGL(set_bits_kernel, dim3((cap_v + 255) / 256, index_heads), dim3(256), 0, st, idx_v, cnt_v, cap_v,
+                       static_cast<int>(n), vbit, w.vw, 0);
+    VS_LAUNCH_CHECK();
+    const int nbits = static_cast<int>((n + 31) / 32 + 1);
+    hipLaunchKernelGGL(block_diag_kernel, dim3((w.tw * 32 + 255) / 256, index_heads), dim3(256), 0, st, sbit, w.sw, t32, w.tw,
+                       nbits);
+    VS_LAUNCH_CHECK();
+
+    AttnParams p{};
+    p.q = static_cast<const uint16_t*>(q);
+    p.k = static_cast<const uint16_t*>(k);
+    p.v = static_cast<const uint16_t*>(v);
+    p.o = static_cast<uint16_t*>(o_bf16);
+    p.lse = lse;
+    p.q_heads = q_heads;
+    p.kv_heads = kv_heads;
+    p.group = q_heads / kv_heads;
+    p.index_per_q = (index_heads == q_heads && q_heads != kv_heads) ? 1 : 0;
+    p.hc = heads_per_workgroup(p.group, p.index_per_q != 0);
+    p.n = static_cast<int>(n);
+    p.scale = scale;
+    p.c = scale * 1.4426950408889634f;
+    p.idx_v = idx_v;
+    p.cnt_v = cnt_v;
+    p.cap_v = cap_v;
+    p.sbit = sbit;
+    p.vbit = vbit;
+    p.t32 = t32;
+    p.sw = w.sw;
+    p.vw = w.vw;
+    p.tw = w.tw;
+    p.tile_counter = reinterpret_cast<unsigned long long*>(base + w.counter_off);
+    return launch_attention<false>(p, st);
+}
+
+int vs_dense_prefill(const void* q, const void* k, const void* v, int q_heads, int kv_heads, int64_t n, float scale,
+                     void* o_bf16, float* lse, void* stream) {
+    int rc = check_qkv(q, k, v, q_heads, kv_heads, n, scale, o_bf16);
+    if (rc != VS_OK) return rc;
+    AttnParams p{};
+    p.q = static_cast<const uint16_t*>(q);
+    p.k = static_cast<const uint16_t*>(k);
+    p.v = static_cast<const uint16_t*>(v);
+    p.o = static_cast<uint16_t*>(o_bf16);
+    p.lse = lse;
+    p.q_heads = q_heads;
+    p.kv_heads = kv_heads;
+    p.group = q_heads / kv_heads;
+    p.index_per_q = 0;
+    p.hc = heads_per_workgroup(p.group, false);
+    p.n = static_cast<int>(n);
+    p.scale = scale;
+    p.c = scale * 1.4426950408889634f;
+    p.tile_counter = nullptr;
+    return launch_attention<true>(p, static_cast<hipStream_t>(stream));
+}
+
+int vs_sparse_prefill_tiles(const void* ws, size_t ws_bytes, void* stream, int64_t* executed_tiles_host) {
+    if (!ws || ws_bytes < 256 || !executed_tiles_host) return VS_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    VS_HIP(hipStreamSynchronize(st));
+    unsigned long long c = 0;
+    VS_HIP(hipMemcpy(&c, ws, sizeof(c), hipMemcpyDeviceToHost));
+    *executed_tiles_host = static_cast<int64_t>(c);
+    return VS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,144 @@
+"""GPU parity: vs_dense_prefill and vs_sparse_prefill (through the C ABI) against the fp64 oracle,
+element by element on the same post-RoPE bf16 buffers.  Tolerance: max-abs 2e-2 on the bf16 outputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2603_04460_amd as vs
+from paper_2603_04460_amd import synth
+from gpu_util import make_qkv, run_sparse, run_dense, lists, check_attention, bf16_to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("hq,hk,n", [(4, 1, 200), (1, 1, 1000), (2, 1, 300), (8, 1, 257), (8, 2, 64), (3, 1, 130),
+                                     (4, 1, 1), (4, 1, 31), (4, 1, 33)])
+def test_dense_small(hq, hk, n):
+    (q, k, v), (qb, kb, vb) = make_qkv(100 + n, hq, hk, n)
+    o, lse = run_dense(q, k, v)
+    ref_o, ref_lse = oracle.dense_attention(qb, kb, vb)
+    check_attention(o, lse, ref_o, ref_lse)
+
+
+def test_config1_single_head_4096_fixed_lists():
+    """Single head, n = 4096, columns {0..3} + 60 random, offsets {0..63} + 64 random; every row checked."""
+    n = 4096
+    seed = synth.config_seed(1)
+    (q, k, v), (qb, kb, vb) = make_qkv(seed, 1, 1, n)
+    iv, cv, is_, cs = synth.fixed_lists(seed, n)
+    o, lse, tiles = run_sparse(q, k, v, iv, cv, is_, cs)
+    ref_o, ref_lse, live = oracle.sparse_attention(qb, kb, vb, iv, cv, is_, cs, return_live=True)
+    check_attention(o, lse, ref_o, ref_lse)
+    assert live.sum() / 1024 <= tiles <= (n // 32) * (n // 32 + 1) // 2
+    # same call twice: bit-identical (no float atomics on the result path)
+    o2, lse2, tiles2 = run_sparse(q, k, v, iv, cv, is_, cs)
+    assert torch.equal(o.view(torch.int16), o2.view(torch.int16)) and torch.equal(lse, lse2) and tiles == tiles2
+
+
+def _random_sets(rng, n, heads, nv, ns, runs=True):
+    sv, ss = [], []
+    for _ in range(heads):
+        cols = set(rng.choice(n, size=min(nv, n), replace=False).tolist())
+        offs = {0}
+        while len(offs) < min(ns, n):
+            start = int(rng.integers(0, n))
+            length = int(rng.integers(1, 40)) if runs else 1
+            offs.update(range(start, min(n, start + length)))
+        sv.append(cols)
+        ss.append(offs)
+    return sv, ss
+
+
+@pytest.mark.parametrize("hq,hk,n,nv,ns,per_q", [
+    (8, 2, 1500, 100, 200, False),     # ragged n, GQA 4, runs + scattered columns (in-block and gathered)
+    (4, 1, 777, 300, 5, False),        # many columns, few diagonals -> gather dominated
+    (4, 4, 640, 20, 60, False),        # G = 1: 256-row tiles
+    (4, 2, 900, 50, 100, False),       # G = 2
+    (8, 2, 700, 40, 80, True),         # one list per query head
+    (16, 2, 500, 30, 50, False),       # G = 8: two workgroups per tile
+])
+def test_sparse_random_lists(hq, hk, n, nv, ns, per_q):
+    rng = np.random.default_rng(n)
+    (q, k, v), (qb, kb, vb) = make_qkv(200 + n, hq, hk, n)
+    ih = hq if per_q else hk
+    sv, ss = _random_sets(rng, n, ih, nv, ns)
+    iv, cv = lists(sv)
+    is_, cs = lists(ss)
+    o, lse, tiles = run_sparse(q, k, v, iv, cv, is_, cs)
+    ref_o, ref_lse, live = oracle.sparse_attention(qb, kb, vb, iv, cv, is_, cs, return_live=True)
+    check_attention(o, lse, ref_o, ref_lse)
+    assert tiles * 1024 >= live.sum()
+
+
+def test_sparse_edge_cases():
+    n, hq, hk = 300, 4, 1
+    (q, k, v), (qb, kb, vb) = make_qkv(7, hq, hk, n)
+    cases = {
+        "diagonal only": ([[]], [[0]]),
+        "columns only, no diagonal: rows before the first column are empty": ([[5, 70, 299]], [[]]),
+        "offset without the diagonal": ([[]], [[3]]),
+        "all offsets = dense": ([[]], [list(range(n))]),
+        "all columns = dense": ([list(range(n))], [[]]),
+        "far offset only touches late rows": ([[0]], [[0, 290]]),
+        "column in the last block": ([[298]], [[0, 1]]),
+    }
+    for name, (sv, ss) in cases.items():
+        iv, cv = lists(sv, cap=n)
+        is_, cs = lists(ss, cap=n)
+        o, lse, _ = run_sparse(q, k, v, iv, cv, is_, cs)
+        ref_o, ref_lse = oracle.sparse_attention(qb, kb, vb, iv, cv, is_, cs)
+        check_attention(o, lse, ref_o, ref_lse)
+    # full budget == the dense kernel's own answer to within rounding of different tile orders
+    iv, cv = lists([[]], cap=4)
+    is_, cs = lists([list(range(n))])
+    o, _, _ = run_sparse(q, k, v, iv, cv, is_, cs)
+    od, _ = run_dense(q, k, v)
+    assert np.abs(bf16_to_f64(o) - bf16_to_f64(od)).max() <= 1e-2
+    # out-of-range and negative entries are ignored
+    iv = np.array([[-5, 3, 9, n, n + 7]], dtype=np.int32); cv = np.array([5], dtype=np.int32)
+    is_ = np.array([[0, 2, n + 1]], dtype=np.int32); cs = np.array([3], dtype=np.int32)
+    o, lse, _ = run_sparse(q, k, v, iv, cv, is_, cs)
+    iv2, cv2 = lists([[3, 9]]); is2, cs2 = lists([[0, 2]])
+    ref_o, ref_lse = oracle.sparse_attention(qb, kb, vb, iv2, cv2, is2, cs2)
+    check_attention(o, lse, ref_o, ref_lse)
+
+
+def test_sparse_many_tiles_sampled_rows():
+    """n = 16384, 8 / 2 heads: several hundred tiles per row block, > 4096 gathered columns (two gather
+    rounds), checked on a declared row sample."""
+    n, hq, hk = 16384, 8, 2
+    rng = np.random.default_rng(5)
+    (q, k, v), (qb, kb, vb) = make_qkv(55, hq, hk, n)
+    sv, ss = _random_sets(rng, n, hk, 6000, 700)
+    iv, cv = lists(sv)
+    is_, cs = lists(ss)
+    o, lse, tiles = run_sparse(q, k, v, iv, cv, is_, cs)
+    rows = synth.sample_rows(5, n, 48, 48, 64)
+    ref_o, ref_lse = oracle.sparse_attention(qb, kb, vb, iv, cv, is_, cs, rows=rows)
+    check_attention(o, lse, ref_o, ref_lse, rows=rows)
+
+
+def test_dense_sampled_rows_8192():
+    n, hq, hk = 8192, 8, 2
+    (q, k, v), (qb, kb, vb) = make_qkv(66, hq, hk, n)
+    o, lse = run_dense(q, k, v)
+    rows = synth.sample_rows(6, n, 32, 32, 32)
+    ref_o, ref_lse = oracle.dense_attention(qb, kb, vb, rows=rows)
+    check_attention(o, lse, ref_o, ref_lse, rows=rows)
+
+
+def test_argument_errors():
+    (q, k, v), _ = make_qkv(1, 4, 1, 64)
+    o = torch.empty_like(q)
+    iv = torch.zeros((1, 4), dtype=torch.int32, device="cuda"); cv = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ws = torch.empty(vs.sparse_prefill_workspace(4, 1, 1, 64), dtype=torch.uint8, device="cuda")
+    with pytest.raises(vs.VsError) as e:
+        vs.sparse_prefill(q, k, v, iv, cv, iv, cv, o, None, ws[:16])
+    assert e.value.code == -3
+    with pytest.raises(vs.VsError) as e:
+        vs.dense_prefill(q[:3].contiguous(), torch.cat([k, k]), torch.cat([v, v]), o[:3].contiguous())
+    assert e.value.code == -2
+    with pytest.raises(vs.VsError) as e:
+        vs.dense_prefill(q, k, v, o, scale=-1.0)
+    assert e.value.code == -1
