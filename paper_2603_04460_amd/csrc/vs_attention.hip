@@ -1,9 +1,11 @@
 // Causal vertical-slash sparse attention and dense causal attention for gfx950.
 //
-// One workgroup (4 wavefronts) owns a query tile of one KV head: 8 "row blocks" of 32 query rows,
-// arranged as hc query heads of the KV group times 8/hc consecutive 32-row sub-blocks.  Each
-// wavefront owns two row blocks (two heads on the same rows when hc >= 2) so that every K / V
-// fragment read from LDS feeds two MFMAs.
+// One workgroup (8 wavefronts, two per SIMD) owns a query tile of one KV head: 8 row blocks of 32
+// query rows, arranged as hc query heads of the KV group times 8/hc consecutive 32-row sub-blocks
+// (hc = 4 for the 4:1 GQA layers: a 64-row tile of all four heads).  K / V tiles are staged once in
+// LDS for all eight row blocks.  Each wavefront owns one row block and stays under 256 VGPRs so that
+// two wavefronts share a SIMD: while one runs its softmax on the vector ALU the other keeps the
+// matrix core busy.
 //
 // Scores are computed transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: a lane then holds
 // 16 keys of ONE query, which makes the row maximum a 16-way in-lane reduction plus one
@@ -21,8 +23,10 @@
 //   3. streams marked blocks (coalesced rows) and gathered columns (row gathers) through LDS and
 //      runs online-softmax attention on them.  The exact element mask
 //          live(i, j) = j <= i and ( offset i-j selected  or  column j selected )
-//      is a 63-bit window of the offset bitmap per 32x32 tile (tile-uniform, held in SGPRs) plus
-//      a 32-bit column word; interior tiles whose window is all ones skip the mask.
+//      is a 63-bit window of the offset bitmap per 32x32 tile plus a 32-bit column word, both
+//      wave-uniform (SGPRs); they are turned into one 64-bit lane mask per accumulator element on the
+//      scalar unit, so masking costs one v_cndmask per element.  Interior tiles whose window is all
+//      ones skip the mask, row blocks whose window is empty skip the tile.
 #include <hip/hip_runtime.h>
 #include <limits.h>
 #include <math.h>
@@ -41,11 +45,13 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kD = 128;
-constexpr int kThreads = 256;
-constexpr int kRowBytes = 288;                 // 256 B of data + 32 B pad: conflict-free b128 and transposing reads
-constexpr int kStageKeys = 64;                 // two 32-key tiles per LDS stage
-constexpr int kTileBytes = 32 * kRowBytes;     // one 32-key tile of K or V
-constexpr int kStageBytes = 2 * 2 * kTileBytes;  // K and V, two tiles
+constexpr int kThreads = 512;
+constexpr int kWaves = kThreads / 64;
+constexpr int kKRow = 272;                     // K row: 256 B + 16 B pad, conflict-free for the 16-byte fragment reads
+constexpr int kVRow = 288;                     // V row: 256 B + 32 B pad, conflict-free for the transposing 8-byte reads
+constexpr int kKTile = 32 * kKRow;             // one 32-key tile of K
+constexpr int kVTile = 32 * kVRow;             // one 32-key tile of V
+constexpr int kStageBytes = 2 * (kKTile + kVTile);   // two tiles of K, then two tiles of V
 constexpr int kListCap = 4096;                 // entries of the per-round tile / gather list
 constexpr int kTbitWords = 1024;               // touched-block bits for up to 32768 key blocks (n <= 2^20)
 constexpr size_t kSmemBytes = 2 * kStageBytes + kListCap * 4 + kTbitWords * 4 + 64;
@@ -88,6 +94,40 @@ __device__ __forceinline__ float half_swap_sum(float x) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ uint64_t uniform64(uint64_t x) {
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(x));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(x >> 32));
+    return (static_cast<uint64_t>(hi) << 32) | lo;
+}
+
+// val where the wave-uniform 64-bit lane mask has this lane's bit set, else dead
+__device__ __forceinline__ float keep_lanes(uint64_t lanemask, float val, float dead) {
+    float out;
+    asm("v_cndmask_b32_e64 %0, %1, %2, %3" : "=v"(out) : "v"(dead), "v"(val), "s"(lanemask));
+    return out;
+}
+
+// Lane mask of accumulator element E of a 32x32 S^T tile: lane (q, h) holds key 8 (E/4) + 4 h + E%4 of query q.
+// w: selected offsets dlt-31 .. dlt+31 at bits 0..62; cz: the causal ones among them; vw: selected columns.
+template <int E>
+__device__ __forceinline__ uint64_t element_lanes(uint64_t w, uint64_t cz, uint32_t vw) {
+    constexpr int kj0 = 8 * (E >> 2) + (E & 3);
+    uint32_t lo = static_cast<uint32_t>(w >> (31 - kj0)), hi = static_cast<uint32_t>(w >> (27 - kj0));
+    if ((vw >> kj0) & 1u) lo |= static_cast<uint32_t>(cz >> (31 - kj0));
+    if ((vw >> (kj0 + 4)) & 1u) hi |= static_cast<uint32_t>(cz >> (27 - kj0));
+    return (static_cast<uint64_t>(hi) << 32) | lo;
+}
+
+template <int E>
+__device__ __forceinline__ void mask_elements(f32x16& acc, uint64_t w, uint64_t cz, uint32_t vw, float dead) {
+    acc[E] = keep_lanes(element_lanes<E>(w, cz, vw), acc[E], dead);
+    if constexpr (E + 1 < 16) mask_elements<E + 1>(acc, w, cz, vw, dead);
+}
+
 // Ordered append of the flagged threads' values to list[base...]; returns the new length.
 __device__ __forceinline__ int wg_append(bool flag, int value, int* list, int base, int* wtot) {
     const uint64_t bal = __ballot(flag);
@@ -97,7 +137,7 @@ __device__ __forceinline__ int wg_append(bool flag, int value, int* list, int ba
     __syncthreads();
     int off = base, tot = 0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < kWaves; ++i) {
         const int c = wtot[i];
         if (i < w) off += c;
         tot += c;
@@ -134,14 +174,11 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     const int n = p.n;
     const int i_last = min(i0 + BQ, n) - 1;
 
-    int slot_head[2], slot_i0[2];
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-        const int rb = 2 * wave + s;
-        slot_head[s] = g * p.group + hchunk * p.hc + rb % p.hc;
-        slot_i0[s] = i0 + 32 * (rb / p.hc);
-    }
-    const int ih = p.index_per_q ? slot_head[0] : g;
+    // this wavefront's row block: 32 rows of one query head
+    const int my_head = g * p.group + hchunk * p.hc + wave % p.hc;
+    const int my_i0 = i0 + 32 * (wave / p.hc);
+    const bool my_rows = my_i0 < n;
+    const int ih = p.index_per_q ? my_head : g;
     const uint32_t* __restrict__ sbit = DENSE ? nullptr : p.sbit + static_cast<size_t>(ih) * p.sw;
     const uint32_t* __restrict__ vbit = DENSE ? nullptr : p.vbit + static_cast<size_t>(ih) * p.vw;
     const uint32_t* __restrict__ t32 = DENSE ? nullptr : p.t32 + static_cast<size_t>(ih) * p.tw;
@@ -150,40 +187,32 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     const uint16_t* __restrict__ vbase = p.v + static_cast<size_t>(g) * n * kD;
 
     // ---- Q fragments: B operand of S^T = K Q^T; lane holds query qi, d = 16 kk + 8 hh .. +7 ----
-    bf16x8 qf[2][8];
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-        const int row = slot_i0[s] + qi;
-        const uint16_t* src = p.q + (static_cast<size_t>(slot_head[s]) * n + min(row, n - 1)) * kD + 8 * hh;
+    bf16x8 qf[8];
+    {
+        const int row = my_i0 + qi;
+        const uint16_t* src = p.q + (static_cast<size_t>(my_head) * n + min(row, n - 1)) * kD + 8 * hh;
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
             uint4 raw = make_uint4(0, 0, 0, 0);
             if (row < n) raw = *reinterpret_cast<const uint4*>(src + 16 * kk);
-            qf[s][kk] = __builtin_bit_cast(bf16x8, raw);
+            qf[kk] = __builtin_bit_cast(bf16x8, raw);
         }
     }
 
-    f32x16 oacc[2][4];
-    float m_run[2], l_run[2];
+    f32x16 oacc[4];
+    float m_run = NEG_INF, l_run = 0.f;
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
-        m_run[s] = NEG_INF;
-        l_run[s] = 0.f;
+    for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) oacc[s][db][e] = 0.f;
-    }
+        for (int e = 0; e < 16; ++e) oacc[db][e] = 0.f;
     unsigned int tiles_done = 0;
 
-    // ---- staging: thread loads chunk (tid & 15) of rows (tid >> 4) + 16 u, u = 0..3 ----
+    // ---- staging: thread loads 16-byte chunk (tid & 15) of row (tid >> 4) of each of the two tiles ----
     const int st_row = tid >> 4, st_chunk = tid & 15;
-    uint4 kreg[4], vreg[4];
-
-    // row_of(u): global key row for staged row st_row + 16 u, or -1
-    auto load_rows = [&](const int (&rows)[4]) __attribute__((always_inline)) {
+    uint4 kreg[2], vreg[2];
+    auto load_rows = [&](const int (&rows)[2]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < 2; ++u) {
             kreg[u] = make_uint4(0, 0, 0, 0);
             vreg[u] = make_uint4(0, 0, 0, 0);
             if (rows[u] >= 0) {
@@ -195,145 +224,110 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     };
     auto store_rows = [&](int buf) __attribute__((always_inline)) {
         unsigned char* kb = kvbuf + buf * kStageBytes;
-        unsigned char* vb = kb + 2 * kTileBytes;
+        unsigned char* vb = kb + 2 * kKTile;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int off = (st_row + 16 * u) * kRowBytes + st_chunk * 16;
-            *reinterpret_cast<uint4*>(kb + off) = kreg[u];
-            *reinterpret_cast<uint4*>(vb + off) = vreg[u];
+        for (int u = 0; u < 2; ++u) {
+            *reinterpret_cast<uint4*>(kb + u * kKTile + st_row * kKRow + st_chunk * 16) = kreg[u];
+            *reinterpret_cast<uint4*>(vb + u * kVTile + st_row * kVRow + st_chunk * 16) = vreg[u];
         }
     };
 
-    // ---- one 32-key tile against both row blocks of this wavefront ----
-    auto compute_tile = [&](const unsigned char* kt, const unsigned char* vt, const bool (&live)[2],
-                            const bool (&need)[2], const uint32_t (&mb)[2]) __attribute__((always_inline)) {
-        if (!live[0] && !live[1]) return;
-        bf16x8 kf[8];
+    // ---- one 32-key tile against this wavefront's row block ----
+    // apply_mask(acc) kills the dead elements (set to -inf) when the tile needs a mask
+    auto compute_tile = [&](const unsigned char* kt, const unsigned char* vt, bool need, auto apply_mask) __attribute__((always_inline)) {
+        ++tiles_done;
+        f32x16 acc;
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk)
-            kf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(kt + qi * kRowBytes + kk * 32 + hh * 16));
-        bf16x8 pb[2][2];
+        for (int e = 0; e < 16; ++e) acc[e] = 0.f;
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            if (!live[s]) continue;
-            ++tiles_done;
-            f32x16 acc;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[s][kk], acc, 0, 0, 0);
-            if (need[s]) {
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int bit = 27 - 8 * (e >> 2) - (e & 3);
-                    if (!((mb[s] >> bit) & 1u)) acc[e] = NEG_INF;
-                }
-            }
-            float mx = acc[0];
-#pragma unroll
-            for (int e = 1; e < 16; ++e) mx = fmaxf(mx, acc[e]);
-            mx = half_swap_max(mx);
-            const float m_new = fmaxf(m_run[s], mx);
-            const bool grow = (m_new - m_run[s]) * p.c > kRescaleThreshold;   // false when both are -inf
-            if (__ballot(grow)) {
-                const float alpha = (m_new == NEG_INF) ? 1.f : __builtin_amdgcn_exp2f((m_run[s] - m_new) * p.c);
-#pragma unroll
-                for (int db = 0; db < 4; ++db)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) oacc[s][db][e] *= alpha;
-                l_run[s] *= alpha;
-                m_run[s] = m_new;
-            }
-            const float mc = (m_run[s] == NEG_INF) ? 0.f : m_run[s] * p.c;
-            float lsum = 0.f;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                acc[e] = __builtin_amdgcn_exp2f(fmaf(acc[e], p.c, -mc));
-                lsum += acc[e];
-            }
-            l_run[s] += lsum;
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int e = 0; e < 8; e += 2) {
-                    f32x2 two = {acc[8 * t + e], acc[8 * t + e + 1]};
-                    bf16x2 r = __builtin_convertvector(two, bf16x2);
-                    pb[s][t][e] = r[0];
-                    pb[s][t][e + 1] = r[1];
-                }
+        for (int kk = 0; kk < 8; ++kk) {
+            const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(kt + qi * kKRow + kk * 32 + hh * 16));
+            acc = mfma32(kf, qf[kk], acc);
         }
+        if (need) apply_mask(acc);
+        float mx = fmaxf(fmaxf(acc[0], acc[1]), acc[2]);
+#pragma unroll
+        for (int e = 3; e < 15; e += 2) mx = fmaxf(fmaxf(mx, acc[e]), acc[e + 1]);
+        mx = fmaxf(mx, acc[15]);
+        mx = half_swap_max(mx);
+        const float m_new = fmaxf(m_run, mx);
+        const bool grow = (m_new - m_run) * p.c > kRescaleThreshold;   // false when both are -inf
+        if (__ballot(grow)) {
+            const float alpha = (m_new == NEG_INF) ? 1.f : __builtin_amdgcn_exp2f((m_run - m_new) * p.c);
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
+            l_run *= alpha;
+            m_run = m_new;
+        }
+        const float mc = (m_run == NEG_INF) ? 0.f : m_run * p.c;
+        float lsum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            acc[e] = __builtin_amdgcn_exp2f(fmaf(acc[e], p.c, -mc));
+            lsum += acc[e];
+        }
+        l_run += lsum;
+        bf16x8 pb[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {
+                const f32x2 two = {acc[8 * t + e], acc[8 * t + e + 1]};
+                const bf16x2 r = __builtin_convertvector(two, bf16x2);
+                pb[t][e] = r[0];
+                pb[t][e + 1] = r[1];
+            }
         // O^T += V^T P^T.  Transposing LDS read: within 16 lanes, lane i addresses row i/4, 4 columns at
         // 4 (i%4); it receives column i of those 4 rows, i.e. 4 consecutive keys of one d.
         const int li = lane & 15, dsel = (lane >> 4) & 1;
+        const unsigned char* va = vt + (4 * hh + (li >> 2)) * kVRow + (16 * dsel + 4 * (li & 3)) * 2;
+        typedef __attribute__((address_space(3))) bf16x4t* lds_ptr_t;
 #pragma unroll
         for (int db = 0; db < 4; ++db) {
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
-                const unsigned char* a0 = vt + (16 * t + 4 * hh + (li >> 2)) * kRowBytes + (32 * db + 16 * dsel + 4 * (li & 3)) * 2;
-                const unsigned char* a1 = a0 + 8 * kRowBytes;
-                typedef __attribute__((address_space(3))) bf16x4t* lds_ptr_t;
-                bf16x4t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr_t)(a0));
-                bf16x4t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr_t)(a1));
+                const unsigned char* a0 = va + 16 * t * kVRow + 64 * db;
+                const bf16x4t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr_t)(a0));
+                const bf16x4t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr_t)(a0 + 8 * kVRow));
                 bf16x8 vf;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     vf[e] = lo[e];
                     vf[4 + e] = hi[e];
                 }
-#pragma unroll
-                for (int s = 0; s < 2; ++s)
-                    if (live[s]) oacc[s][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[s][t], oacc[s][db], 0, 0, 0);
+                oacc[db] = mfma32(vf, pb[t], oacc[db]);
             }
         }
     };
 
-    // ---- per-tile mask words ----
     // contiguous block b (keys 32 b .. 32 b + 31)
-    auto block_masks = [&](int b, bool (&live)[2], bool (&need)[2], uint32_t (&mb)[2]) __attribute__((always_inline)) {
-        const int j0 = 32 * b;
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            const int dlt = slot_i0[s] - j0;                 // offset of (row 0, key 0) of the 32x32 tile
-            live[s] = false;
-            need[s] = false;
-            mb[s] = 0;
-            if (dlt < -31 || slot_i0[s] >= n) continue;      // every key lies after every row / padding rows
-            const uint64_t cz = dlt >= 31 ? kAll63 : ((kAll63 << (31 - dlt)) & kAll63);   // offsets >= 0
-            uint64_t w;
-            uint32_t vw = 0;
-            if (DENSE) {
-                w = cz;
-            } else {
-                w = window64(sbit, dlt + 33) & kAll63;       // offsets dlt-31 .. dlt+31 at bits 0..62 (64-bit guard in front)
-                vw = vbit[b];
-            }
-            live[s] = (w | (vw ? cz : 0ull)) != 0ull;
-            need[s] = w != kAll63;
-            const int sh = 4 + qi - 4 * hh;
-            const uint32_t wl = static_cast<uint32_t>(w >> sh), cl = static_cast<uint32_t>(cz >> sh);
-            const uint32_t vl = __builtin_bitreverse32(vw) >> (4 - 4 * hh);
-            mb[s] = wl | (vl & cl);
-        }
+    auto block_tile = [&](int b, const unsigned char* kt, const unsigned char* vt) __attribute__((always_inline)) {
+        const int dlt = my_i0 - 32 * b;                      // offset of (row 0, key 0) of the 32x32 tile
+        if (dlt < -31 || !my_rows) return;                   // every key lies after every row / padding rows
+        const uint64_t cz = dlt >= 31 ? kAll63 : ((kAll63 << (31 - dlt)) & kAll63);   // offsets >= 0
+        // offsets dlt-31 .. dlt+31 at bits 0..62 (the bitmap has a 64-bit guard in front)
+        const uint64_t w = DENSE ? cz : uniform64(window64(sbit, dlt + 33) & kAll63);
+        const uint32_t vw = DENSE ? 0u : static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(vbit[b]));
+        if ((w | (vw ? cz : 0ull)) == 0ull) return;          // nothing live for this row block
+        compute_tile(kt, vt, w != kAll63, [&](f32x16& acc) __attribute__((always_inline)) { mask_elements<0>(acc, w, cz, vw, NEG_INF); });
     };
     // gathered tile: 32 columns at cols[0..31] (ascending, INT_MAX padding)
-    auto gather_masks = [&](const int* cols, bool (&live)[2], bool (&need)[2], uint32_t (&mb)[2]) __attribute__((always_inline)) {
+    auto gather_tile = [&](const int* cols, const unsigned char* kt, const unsigned char* vt) __attribute__((always_inline)) {
         const int cmin = cols[0], cmax = cols[31];
-        int c[16];
+        if (cmin > my_i0 + 31 || !my_rows) return;
+        compute_tile(kt, vt, cmax > my_i0, [&](f32x16& acc) __attribute__((always_inline)) {
+            const int row = my_i0 + qi;
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            const int4 c4 = *reinterpret_cast<const int4*>(cols + 8 * a + 4 * hh);
-            c[4 * a] = c4.x; c[4 * a + 1] = c4.y; c[4 * a + 2] = c4.z; c[4 * a + 3] = c4.w;
-        }
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            live[s] = cmin <= slot_i0[s] + 31 && slot_i0[s] < n;
-            need[s] = cmax > slot_i0[s];
-            const int row = slot_i0[s] + qi;
-            uint32_t m = 0;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) m |= (c[e] <= row ? 1u : 0u) << (27 - 8 * (e >> 2) - (e & 3));
-            mb[s] = m;
-        }
+            for (int a = 0; a < 4; ++a) {
+                const int4 c4 = *reinterpret_cast<const int4*>(cols + 8 * a + 4 * hh);
+                if (c4.x > row) acc[4 * a] = NEG_INF;
+                if (c4.y > row) acc[4 * a + 1] = NEG_INF;
+                if (c4.z > row) acc[4 * a + 2] = NEG_INF;
+                if (c4.w > row) acc[4 * a + 3] = NEG_INF;
+            }
+        });
     };
 
     // ---- software pipeline over the tiles of one phase ----
@@ -342,26 +336,25 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
         constexpr bool GATHER = decltype(gather_tag)::value;
         const int nstages = (ntiles + 1) >> 1;
         if (nstages == 0) return;
-        auto stage_rows = [&](int st, int (&rows)[4]) __attribute__((always_inline)) {
+        auto stage_rows = [&](int st, int (&rows)[2]) __attribute__((always_inline)) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int r = st_row + 16 * u;
-                const int t = 2 * st + (r >> 5);
+            for (int u = 0; u < 2; ++u) {
+                const int t = 2 * st + u;
                 int row = -1;
                 if (t < ntiles) {
                     if (GATHER) {
-                        const int col = list[32 * t + (r & 31)];
+                        const int col = list[32 * t + st_row];
                         row = col < n ? col : -1;
                     } else {
                         const int b = DENSE ? t : list[t];
-                        row = 32 * b + (r & 31);
+                        row = 32 * b + st_row;
                         if (row >= n) row = -1;
                     }
                 }
                 rows[u] = row;
             }
         };
-        int rows[4];
+        int rows[2];
         stage_rows(0, rows);
         load_rows(rows);
         store_rows(0);
@@ -373,20 +366,13 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
                 load_rows(rows);
             }
             const unsigned char* kb = kvbuf + (st & 1) * kStageBytes;
-            const unsigned char* vb = kb + 2 * kTileBytes;
+            const unsigned char* vb = kb + 2 * kKTile;
 #pragma unroll
             for (int tt = 0; tt < 2; ++tt) {
                 const int t = 2 * st + tt;
                 if (t < ntiles) {
-                    bool live[2], need[2];
-                    uint32_t mb[2];
-                    if (GATHER) {
-                        gather_masks(list + 32 * t, live, need, mb);
-                    } else {
-                        const int b = __builtin_amdgcn_readfirstlane(DENSE ? t : list[t]);
-                        block_masks(b, live, need, mb);
-                    }
-                    compute_tile(kb + tt * kTileBytes, vb + tt * kTileBytes, live, need, mb);
+                    if (GATHER) gather_tile(list + 32 * t, kb + tt * kKTile, vb + tt * kVTile);
+                    else block_tile(__builtin_amdgcn_readfirstlane(DENSE ? t : list[t]), kb + tt * kKTile, vb + tt * kVTile);
                 }
             }
             if (more) store_rows((st + 1) & 1);
@@ -457,29 +443,27 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     }
 
     // ---- epilogue: O = O^T / l, bf16 store; lse = m * scale + ln(l) ----
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-        const float l_tot = half_swap_sum(l_run[s]);
+    {
+        const float l_tot = half_swap_sum(l_run);
         const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-        const int row = slot_i0[s] + qi;
+        const int row = my_i0 + qi;
         if (row < n) {
-            uint16_t* dst = p.o + (static_cast<size_t>(slot_head[s]) * n + row) * kD;
+            uint16_t* dst = p.o + (static_cast<size_t>(my_head) * n + row) * kD;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
                 for (int a = 0; a < 4; ++a) {
-                    f32x2 x01 = {oacc[s][db][4 * a] * inv, oacc[s][db][4 * a + 1] * inv};
-                    f32x2 x23 = {oacc[s][db][4 * a + 2] * inv, oacc[s][db][4 * a + 3] * inv};
-                    bf16x2 y01 = __builtin_convertvector(x01, bf16x2);
-                    bf16x2 y23 = __builtin_convertvector(x23, bf16x2);
+                    const f32x2 x01 = {oacc[db][4 * a] * inv, oacc[db][4 * a + 1] * inv};
+                    const f32x2 x23 = {oacc[db][4 * a + 2] * inv, oacc[db][4 * a + 3] * inv};
+                    const bf16x2 y01 = __builtin_convertvector(x01, bf16x2);
+                    const bf16x2 y23 = __builtin_convertvector(x23, bf16x2);
                     uint2 out;
                     out.x = __builtin_bit_cast(uint32_t, y01);
                     out.y = __builtin_bit_cast(uint32_t, y23);
                     *reinterpret_cast<uint2*>(dst + 32 * db + 8 * a + 4 * hh) = out;
                 }
             if (p.lse && hh == 0)
-                p.lse[static_cast<size_t>(slot_head[s]) * n + row] =
-                    l_tot > 0.f ? m_run[s] * p.scale + __logf(l_tot) : NEG_INF;
+                p.lse[static_cast<size_t>(my_head) * n + row] = l_tot > 0.f ? m_run * p.scale + __logf(l_tot) : NEG_INF;
         }
     }
     if (p.tile_counter && lane == 0 && tiles_done) atomicAdd(p.tile_counter, static_cast<unsigned long long>(tiles_done));
