@@ -56,6 +56,8 @@ class Workload:
         self.q, self.k = synth.plant_heavy_hitters(self.q, self.k, u, cols)
         W = synth.indexer_weights(seed, d_h, act)
         self.W_host = W
+        d_s, d_v = synth.score_structure_profile(seed, hk, n, cols)
+        self.k, self.v = synth.plant_score_structure(self.k, self.v, W[0], W[2], W[3], d_s, d_v)
         self.weights = vs.IndexerWeights(*[torch.from_numpy(x).cuda() for x in W], 0.0, 0.0, act)
         self.cap = min(n, max(4096, n // 4))
         self.budget = vs.Budget(mode=0, tau_v=tau, tau_s=tau, n_sink=min(4, n), n_local=min(64, n), cap_v=self.cap, cap_s=self.cap)
@@ -207,7 +209,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "C%d: one 4B-shaped GQA layer (32 q heads / 8 KV heads, head_dim 128), n=%d, RoPE theta=%g, "
-                               "heavy hitters + local structure, VSIndexer(d_h=256, GELU) -> tau=%.2f budget (4 sinks, 64 local) -> "
+                               "heavy hitters + local structure + planted score bands, VSIndexer(d_h=256, GELU) -> tau=%.2f budget (4 sinks, 64 local) -> "
                                "fused sparse attention" % (args.config, n, w.theta, args.tau),
                    "seq_len": n, "q_heads": hq, "kv_heads": w.hk, "tau": args.tau},
         "ms_per_layer": {"indexer": t_idx, "select": t_sel, "sparse_attention": t_att, "step": ms_step,

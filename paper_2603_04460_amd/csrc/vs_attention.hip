@@ -48,7 +48,7 @@ constexpr int kD = 128;
 constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / 64;
 constexpr int kKRow = 272;                     // K row: 256 B + 16 B pad, conflict-free for the 16-byte fragment reads
-constexpr int kVRow = 288;                     // V row: 256 B + 32 B pad, conflict-free for the transposing 8-byte reads
+constexpr int kVRow = 320;                     // V row: 256 B + 64 B pad: the 4 rows x 64 B of a transposing read tile all 64 banks
 constexpr int kKTile = 32 * kKRow;             // one 32-key tile of K
 constexpr int kVTile = 32 * kVRow;             // one 32-key tile of V
 constexpr int kStageBytes = 2 * (kKTile + kVTile);   // two tiles of K, then two tiles of V
@@ -162,9 +162,12 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     const float NEG_INF = -INFINITY;
 
     // ---- which tile ----
+    // Workgroups are dealt to the 8 XCDs round-robin.  Dense: KV head = bid % kv_heads keeps a head's K / V in one
+    // XCD's L2 (every head has the same work).  Sparse: heads differ in budget, so the head rotates with the tile
+    // index and every XCD gets an equal share of every head.
     const int bid = blockIdx.x;
-    const int g = bid % p.kv_heads;
     const int rest = bid / p.kv_heads;
+    const int g = DENSE ? bid % p.kv_heads : (bid + rest) % p.kv_heads;
     const int hchunks = p.group / p.hc;
     const int hchunk = rest % hchunks;
     const int tile = p.tiles - 1 - rest / hchunks;          // longest tiles first
@@ -236,14 +239,37 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     // apply_mask(acc) kills the dead elements (set to -inf) when the tile needs a mask
     auto compute_tile = [&](const unsigned char* kt, const unsigned char* vt, bool need, auto apply_mask) __attribute__((always_inline)) {
         ++tiles_done;
+        // all K and V fragments of the tile are requested up front: the K reads are waited for by the first
+        // product, the V reads land while the softmax runs
+        bf16x8 kf[8];
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk)
+            kf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(kt + qi * kKRow + kk * 32 + hh * 16));
+        const int li = lane & 15, dsel = (lane >> 4) & 1;
+        const unsigned char* va = vt + (4 * hh + (li >> 2)) * kVRow + (16 * dsel + 4 * (li & 3)) * 2;
+        typedef __attribute__((address_space(3))) bf16x4t* lds_ptr_t;
+        bf16x8 vf[4][2];
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                // transposing LDS read: within 16 lanes, lane i addresses row i/4, 4 columns at 4 (i%4); it receives
+                // column i of those 4 rows, i.e. 4 consecutive keys of one d
+                const unsigned char* a0 = va + 16 * t * kVRow + 64 * db;
+                const bf16x4t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr_t)(a0));
+                const bf16x4t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr_t)(a0 + 8 * kVRow));
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    vf[db][t][e] = lo[e];
+                    vf[db][t][4 + e] = hi[e];
+                }
+            }
+        __builtin_amdgcn_sched_barrier(0);
         f32x16 acc;
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[e] = 0.f;
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(kt + qi * kKRow + kk * 32 + hh * 16));
-            acc = mfma32(kf, qf[kk], acc);
-        }
+        for (int kk = 0; kk < 8; ++kk) acc = mfma32(kf[kk], qf[kk], acc);
         if (need) apply_mask(acc);
         float mx = fmaxf(fmaxf(acc[0], acc[1]), acc[2]);
 #pragma unroll
@@ -279,27 +305,11 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
                 pb[t][e] = r[0];
                 pb[t][e + 1] = r[1];
             }
-        // O^T += V^T P^T.  Transposing LDS read: within 16 lanes, lane i addresses row i/4, 4 columns at
-        // 4 (i%4); it receives column i of those 4 rows, i.e. 4 consecutive keys of one d.
-        const int li = lane & 15, dsel = (lane >> 4) & 1;
-        const unsigned char* va = vt + (4 * hh + (li >> 2)) * kVRow + (16 * dsel + 4 * (li & 3)) * 2;
-        typedef __attribute__((address_space(3))) bf16x4t* lds_ptr_t;
+        // O^T += V^T P^T
 #pragma unroll
-        for (int db = 0; db < 4; ++db) {
+        for (int db = 0; db < 4; ++db)
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const unsigned char* a0 = va + 16 * t * kVRow + 64 * db;
-                const bf16x4t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr_t)(a0));
-                const bf16x4t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr_t)(a0 + 8 * kVRow));
-                bf16x8 vf;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    vf[e] = lo[e];
-                    vf[4 + e] = hi[e];
-                }
-                oacc[db] = mfma32(vf, pb[t], oacc[db]);
-            }
-        }
+            for (int t = 0; t < 2; ++t) oacc[db] = mfma32(vf[db][t], pb[t], oacc[db]);
     };
 
     // contiguous block b (keys 32 b .. 32 b + 31)

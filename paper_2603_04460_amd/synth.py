@@ -148,3 +148,43 @@ def sample_rows(seed, n, first=64, last=64, rand=128):
     first, last = min(first, n), min(last, n)
     mid = rng.choice(n, size=min(rand, n), replace=False)
     return np.unique(np.concatenate([np.arange(first), np.arange(n - last, n), mid])).astype(np.int64)
+
+
+def score_structure_profile(seed, kv_heads, n, hh_cols, local_peak=12.0, n_bands=6, band_peak=(9.0, 12.0),
+                            sink_peak=12.0, hh_peak=9.0):
+    """Nominal logit boosts [kv_heads, n] (float64) that give the indexer's scores the structure the paper
+    describes for real attention maps: for the slash direction a near-diagonal band that decays over
+    ~n/128 offsets plus `n_bands` narrow long-range bands (width n/4096 .. n/2048) at seeded offsets; for the
+    vertical direction the first four columns (sinks) and the planted heavy-hitter columns `hh_cols`."""
+    rng = np.random.default_rng(seed * 7 + 5)
+    t = np.arange(n, dtype=np.float64)
+    d_s = np.zeros((kv_heads, n))
+    d_v = np.zeros((kv_heads, n))
+    for g in range(kv_heads):
+        d_s[g] = local_peak * np.exp(-t / (n / 128.0))
+        for _ in range(n_bands):
+            c = rng.uniform(0.03 * n, 0.97 * n)
+            w = rng.uniform(n / 4096.0, n / 2048.0)
+            d_s[g] += rng.uniform(*band_peak) * np.exp(-0.5 * ((t - c) / w) ** 2)
+        d_v[g, :min(4, n)] = sink_peak
+        d_v[g, np.asarray(hh_cols[g])] = hh_peak
+    return d_s, d_v
+
+
+def plant_score_structure(k, v, W_U, W_V, W_S, d_s, d_v):
+    """Adds, to token t of [K || V], d_s[t] * e_S + d_v[t] * e_V where e_S = W_U W_S / (0.5 |W_U W_S|^2) is the
+    input direction whose unit multiple moves the slash logit by about one (first-order response of the
+    two-layer net with a GELU / SiLU slope of about one half), likewise e_V for the vertical logit.  Applied to
+    post-RoPE K and to V; bf16 in, bf16 out, any device.  A recipe for inputs only: it evaluates no score."""
+    dev = k.device
+    wu = torch.from_numpy(np.asarray(W_U, dtype=np.float64))
+    e = []
+    for wd in (W_S, W_V):
+        d = wu @ torch.from_numpy(np.asarray(wd, dtype=np.float64))
+        e.append((d / (0.5 * d.dot(d))).to(torch.float32).to(dev))
+    a_s = torch.as_tensor(d_s, dtype=torch.float32, device=dev).unsqueeze(-1)
+    a_v = torch.as_tensor(d_v, dtype=torch.float32, device=dev).unsqueeze(-1)
+    add = a_s * e[0] + a_v * e[1]                       # [hk, n, 256]
+    k2 = (k.float() + add[..., :128]).to(torch.bfloat16)
+    v2 = (v.float() + add[..., 128:]).to(torch.bfloat16)
+    return k2, v2
