@@ -51,10 +51,17 @@ constexpr int kKRow = 272;                     // K row: 256 B + 16 B pad, confl
 constexpr int kVRow = 320;                     // V row: 256 B + 64 B pad: the 4 rows x 64 B of a transposing read tile all 64 banks
 constexpr int kKTile = 32 * kKRow;             // one 32-key tile of K
 constexpr int kVTile = 32 * kVRow;             // one 32-key tile of V
-constexpr int kStageBytes = 2 * (kKTile + kVTile);   // two tiles of K, then two tiles of V
-constexpr int kListCap = 4096;                 // entries of the per-round tile / gather list
+constexpr int kSlotBytes = kKTile + kVTile;    // one LDS slot: a K tile, then the V tile of the same keys
+constexpr int kSlots = 6;                      // ring of three stages of two tiles
+constexpr int kListCap = 2048;                 // entries of the per-round gather list; block list: kListCap / nsub entries
 constexpr int kTbitWords = 1024;               // touched-block bits for up to 32768 key blocks (n <= 2^20)
-constexpr size_t kSmemBytes = 2 * kStageBytes + kListCap * 4 + kTbitWords * 4 + 64;
+// ring | list (block numbers or gathered columns) | column word per listed block | offset windows per (sub-block, listed block) | touched bits | scratch
+constexpr size_t kListOff = kSlots * kSlotBytes;
+constexpr size_t kListVwOff = kListOff + kListCap * 4;
+constexpr size_t kListWOff = kListVwOff + (kListCap / 2) * 4;
+constexpr size_t kTbitOff = kListWOff + kListCap * 8;
+constexpr size_t kScratchOff = kTbitOff + kTbitWords * 4;
+constexpr size_t kSmemBytes = kScratchOff + 64;
 constexpr uint64_t kAll63 = 0x7fffffffffffffffull;
 constexpr float kRescaleThreshold = 8.0f;      // log2 units: stale maxima up to 2^8 are tolerated
 
@@ -151,9 +158,11 @@ template <bool DENSE>
 __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams p) {
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char* const kvbuf = smem;
-    int* const list = reinterpret_cast<int*>(smem + 2 * kStageBytes);
-    uint32_t* const tbits = reinterpret_cast<uint32_t*>(smem + 2 * kStageBytes + kListCap * 4);
-    int* const wtot = reinterpret_cast<int*>(smem + 2 * kStageBytes + kListCap * 4 + kTbitWords * 4);
+    int* const list = reinterpret_cast<int*>(smem + kListOff);
+    uint32_t* const list_vw = reinterpret_cast<uint32_t*>(smem + kListVwOff);
+    uint64_t* const list_w = reinterpret_cast<uint64_t*>(smem + kListWOff);
+    uint32_t* const tbits = reinterpret_cast<uint32_t*>(smem + kTbitOff);
+    int* const wtot = reinterpret_cast<int*>(smem + kScratchOff);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -210,10 +219,10 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
         for (int e = 0; e < 16; ++e) oacc[db][e] = 0.f;
     unsigned int tiles_done = 0;
 
-    // ---- staging: thread loads 16-byte chunk (tid & 15) of row (tid >> 4) of each of the two tiles ----
+    // ---- staging: a stage is two 32-key tiles; thread moves 16-byte chunk (tid & 15) of row (tid >> 4) of K and V of each ----
     const int st_row = tid >> 4, st_chunk = tid & 15;
     uint4 kreg[2], vreg[2];
-    auto load_rows = [&](const int (&rows)[2]) __attribute__((always_inline)) {
+    auto load_stage = [&](const int (&rows)[2]) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             kreg[u] = make_uint4(0, 0, 0, 0);
@@ -225,77 +234,67 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
             }
         }
     };
-    auto store_rows = [&](int buf) __attribute__((always_inline)) {
-        unsigned char* kb = kvbuf + buf * kStageBytes;
-        unsigned char* vb = kb + 2 * kKTile;
+    // buf: which of the three stage buffers (0..2)
+    auto store_stage = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            *reinterpret_cast<uint4*>(kb + u * kKTile + st_row * kKRow + st_chunk * 16) = kreg[u];
-            *reinterpret_cast<uint4*>(vb + u * kVTile + st_row * kVRow + st_chunk * 16) = vreg[u];
+            unsigned char* kb = kvbuf + (2 * buf + u) * kSlotBytes;
+            *reinterpret_cast<uint4*>(kb + st_row * kKRow + st_chunk * 16) = kreg[u];
+            *reinterpret_cast<uint4*>(kb + kKTile + st_row * kVRow + st_chunk * 16) = vreg[u];
         }
     };
 
-    // ---- one 32-key tile against this wavefront's row block ----
-    // apply_mask(acc) kills the dead elements (set to -inf) when the tile needs a mask
-    auto compute_tile = [&](const unsigned char* kt, const unsigned char* vt, bool need, auto apply_mask) __attribute__((always_inline)) {
-        ++tiles_done;
-        // all K and V fragments of the tile are requested up front: the K reads are waited for by the first
-        // product, the V reads land while the softmax runs
-        bf16x8 kf[8];
+    // ---- pieces of one (row block, 32-key tile) unit ----
+    const int li = lane & 15, dsel = (lane >> 4) & 1;
+    const int k_off = qi * kKRow + hh * 16;
+    const int v_off = kKTile + (4 * hh + (li >> 2)) * kVRow + (16 * dsel + 4 * (li & 3)) * 2;
+    typedef __attribute__((address_space(3))) bf16x4t* lds_ptr_t;
+    // slot: which of the six tile slots (wave-uniform)
+    auto read_k = [&](int slot, bf16x8 (&kf)[8]) __attribute__((always_inline)) {
+        const unsigned char* kt = kvbuf + slot * kSlotBytes + k_off;
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk)
-            kf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(kt + qi * kKRow + kk * 32 + hh * 16));
-        const int li = lane & 15, dsel = (lane >> 4) & 1;
-        const unsigned char* va = vt + (4 * hh + (li >> 2)) * kVRow + (16 * dsel + 4 * (li & 3)) * 2;
-        typedef __attribute__((address_space(3))) bf16x4t* lds_ptr_t;
-        bf16x8 vf[4][2];
+        for (int kk = 0; kk < 8; ++kk) kf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(kt + kk * 32));
+    };
+    // transposing LDS read: within 16 lanes, lane i addresses row i/4, 4 columns at 4 (i%4); it receives column i of
+    // those 4 rows, i.e. 4 consecutive keys of one d
+    auto read_v = [&](int slot, bf16x8 (&vf)[8]) __attribute__((always_inline)) {
+        const unsigned char* va = kvbuf + slot * kSlotBytes + v_off;
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+        for (int j = 0; j < 8; ++j) {                      // j = 2 db + t16: d block db, keys 16 t16 ..
+            const unsigned char* a0 = va + 16 * (j & 1) * kVRow + 64 * (j >> 1);
+            const bf16x4t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr_t)(a0));
+            const bf16x4t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr_t)(a0 + 8 * kVRow));
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                // transposing LDS read: within 16 lanes, lane i addresses row i/4, 4 columns at 4 (i%4); it receives
-                // column i of those 4 rows, i.e. 4 consecutive keys of one d
-                const unsigned char* a0 = va + 16 * t * kVRow + 64 * db;
-                const bf16x4t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr_t)(a0));
-                const bf16x4t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr_t)(a0 + 8 * kVRow));
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    vf[db][t][e] = lo[e];
-                    vf[db][t][4 + e] = hi[e];
-                }
+            for (int e = 0; e < 4; ++e) {
+                vf[j][e] = lo[e];
+                vf[j][4 + e] = hi[e];
             }
-        __builtin_amdgcn_sched_barrier(0);
-        f32x16 acc;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) acc = mfma32(kf[kk], qf[kk], acc);
-        if (need) apply_mask(acc);
+        }
+    };
+    auto tile_max = [&](const f32x16& acc) __attribute__((always_inline)) -> float {
         float mx = fmaxf(fmaxf(acc[0], acc[1]), acc[2]);
 #pragma unroll
         for (int e = 3; e < 15; e += 2) mx = fmaxf(fmaxf(mx, acc[e]), acc[e + 1]);
-        mx = fmaxf(mx, acc[15]);
-        mx = half_swap_max(mx);
-        const float m_new = fmaxf(m_run, mx);
-        const bool grow = (m_new - m_run) * p.c > kRescaleThreshold;   // false when both are -inf
-        if (__ballot(grow)) {
-            const float alpha = (m_new == NEG_INF) ? 1.f : __builtin_amdgcn_exp2f((m_run - m_new) * p.c);
+        return fmaxf(mx, acc[15]);
+    };
+    auto rescale = [&](float m_new) __attribute__((always_inline)) {
+        const float alpha = (m_new == NEG_INF) ? 1.f : __builtin_amdgcn_exp2f((m_run - m_new) * p.c);
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < 4; ++db)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
-            l_run *= alpha;
-            m_run = m_new;
-        }
-        const float mc = (m_run == NEG_INF) ? 0.f : m_run * p.c;
-        float lsum = 0.f;
+            for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
+        l_run *= alpha;
+        m_run = m_new;
+    };
+    // p = exp2(c s - c m) for elements [E0, E1) of acc, row sum into lsum
+    auto exp_part = [&](f32x16& acc, int e0, int e1, float mc, float& lsum) __attribute__((always_inline)) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
+        for (int e = e0; e < e1; ++e) {
             acc[e] = __builtin_amdgcn_exp2f(fmaf(acc[e], p.c, -mc));
             lsum += acc[e];
         }
-        l_run += lsum;
-        bf16x8 pb[2];
+    };
+    auto pack_p = [&](const f32x16& acc, bf16x8 (&pb)[2]) __attribute__((always_inline)) {
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -305,89 +304,185 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
                 pb[t][e] = r[0];
                 pb[t][e + 1] = r[1];
             }
-        // O^T += V^T P^T
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int t = 0; t < 2; ++t) oacc[db] = mfma32(vf[db][t], pb[t], oacc[db]);
     };
 
-    // contiguous block b (keys 32 b .. 32 b + 31)
-    auto block_tile = [&](int b, const unsigned char* kt, const unsigned char* vt) __attribute__((always_inline)) {
-        const int dlt = my_i0 - 32 * b;                      // offset of (row 0, key 0) of the 32x32 tile
-        if (dlt < -31 || !my_rows) return;                   // every key lies after every row / padding rows
-        const uint64_t cz = dlt >= 31 ? kAll63 : ((kAll63 << (31 - dlt)) & kAll63);   // offsets >= 0
-        // offsets dlt-31 .. dlt+31 at bits 0..62 (the bitmap has a 64-bit guard in front)
-        const uint64_t w = DENSE ? cz : uniform64(window64(sbit, dlt + 33) & kAll63);
-        const uint32_t vw = DENSE ? 0u : static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(vbit[b]));
-        if ((w | (vw ? cz : 0ull)) == 0ull) return;          // nothing live for this row block
-        compute_tile(kt, vt, w != kAll63, [&](f32x16& acc) __attribute__((always_inline)) { mask_elements<0>(acc, w, cz, vw, NEG_INF); });
+    // per-wavefront description of a tile: live (anything kept for this row block), need (a mask is required)
+    struct TileInfo {
+        bool live, need;
+        uint64_t w, cz;          // contiguous tile: selected offsets / causal offsets window
+        uint32_t vw;             // contiguous tile: selected columns of the block
+        const int* cols;         // gathered tile: its 32 column numbers in LDS
     };
-    // gathered tile: 32 columns at cols[0..31] (ascending, INT_MAX padding)
-    auto gather_tile = [&](const int* cols, const unsigned char* kt, const unsigned char* vt) __attribute__((always_inline)) {
-        const int cmin = cols[0], cmax = cols[31];
-        if (cmin > my_i0 + 31 || !my_rows) return;
-        compute_tile(kt, vt, cmax > my_i0, [&](f32x16& acc) __attribute__((always_inline)) {
+    const int bcap = kListCap / nsub;                        // listed blocks per round
+    const int my_sub = wave / p.hc;
+    // t: position in the block list (sparse) or the block number itself (dense)
+    auto block_info = [&](int t) __attribute__((always_inline)) -> TileInfo {
+        TileInfo ti{false, false, 0ull, 0ull, 0u, nullptr};
+        const int b = DENSE ? t : __builtin_amdgcn_readfirstlane(list[t]);
+        const int dlt = my_i0 - 32 * b;                      // offset of (row 0, key 0) of the 32x32 tile
+        if (dlt < -31 || !my_rows) return ti;                // every key lies after every row / padding rows
+        ti.cz = dlt >= 31 ? kAll63 : ((kAll63 << (31 - dlt)) & kAll63);   // offsets >= 0
+        // selected offsets dlt-31 .. dlt+31 at bits 0..62 and the block's column word, both prepared with the list
+        ti.w = DENSE ? ti.cz : uniform64(list_w[my_sub * bcap + t]);
+        ti.vw = DENSE ? 0u : static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(list_vw[t]));
+        ti.live = (ti.w | (ti.vw ? ti.cz : 0ull)) != 0ull;
+        ti.need = ti.w != kAll63;
+        return ti;
+    };
+    auto gather_info = [&](const int* cols) __attribute__((always_inline)) -> TileInfo {
+        TileInfo ti{false, false, 0ull, 0ull, 0u, cols};
+        const int cmin = cols[0], cmax = cols[31];           // ascending, INT_MAX padding
+        ti.live = my_rows && cmin <= my_i0 + 31;
+        ti.need = cmax > my_i0;
+        return ti;
+    };
+    auto apply_mask = [&](f32x16& acc, const TileInfo& ti, auto gather_tag) __attribute__((always_inline)) {
+        if (!ti.need) return;
+        if constexpr (decltype(gather_tag)::value) {
             const int row = my_i0 + qi;
 #pragma unroll
             for (int a = 0; a < 4; ++a) {
-                const int4 c4 = *reinterpret_cast<const int4*>(cols + 8 * a + 4 * hh);
+                const int4 c4 = *reinterpret_cast<const int4*>(ti.cols + 8 * a + 4 * hh);
                 if (c4.x > row) acc[4 * a] = NEG_INF;
                 if (c4.y > row) acc[4 * a + 1] = NEG_INF;
                 if (c4.z > row) acc[4 * a + 2] = NEG_INF;
                 if (c4.w > row) acc[4 * a + 3] = NEG_INF;
             }
-        });
+        } else {
+            mask_elements<0>(acc, ti.w, ti.cz, ti.vw, NEG_INF);
+        }
     };
 
-    // ---- software pipeline over the tiles of one phase ----
-    // GATHER == false: tile t is key block (DENSE ? t : list[t]);  GATHER == true: tile t is list[32 t .. 32 t + 31]
+    // ---- pipeline over the tiles of one phase ----
+    // GATHER == false: tile t is key block (DENSE ? t : list[t]);  GATHER == true: tile t is list[32 t .. 32 t + 31].
+    // A stage is two tiles (64 keys).  Three stages live in LDS: step s computes on stage s, prefetches K fragments of
+    // stage s+1 (complete since the last barrier) and refills the buffer of stage s-1 with stage s+2, whose global loads
+    // were started at the top of the step.  One barrier per step.  The two tiles of a stage go through one softmax
+    // (one row maximum, one rescale decision) and their matrix products are issued as independent chains.
     auto run_phase = [&](int ntiles, auto gather_tag) __attribute__((always_inline)) {
         constexpr bool GATHER = decltype(gather_tag)::value;
+        if (ntiles == 0) return;
         const int nstages = (ntiles + 1) >> 1;
-        if (nstages == 0) return;
         auto stage_rows = [&](int st, int (&rows)[2]) __attribute__((always_inline)) {
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 const int t = 2 * st + u;
                 int row = -1;
                 if (t < ntiles) {
-                    if (GATHER) {
-                        const int col = list[32 * t + st_row];
-                        row = col < n ? col : -1;
-                    } else {
-                        const int b = DENSE ? t : list[t];
-                        row = 32 * b + st_row;
-                        if (row >= n) row = -1;
-                    }
+                    row = GATHER ? list[32 * t + st_row] : 32 * (DENSE ? t : list[t]) + st_row;
+                    if (row >= n) row = -1;
                 }
                 rows[u] = row;
             }
         };
+        auto info = [&](int t) __attribute__((always_inline)) -> TileInfo {
+            if (t >= ntiles) return TileInfo{false, false, 0ull, 0ull, 0u, nullptr};
+            if (GATHER) return gather_info(list + 32 * t);
+            return block_info(t);
+        };
+        // Every vector memory load issued so far (the Q fragments) is waited for here, once.  Left pending, the first
+        // use of Q inside the loop would wait for "all loads", including the staging loads issued just before it.
+        __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0), other counters untouched
         int rows[2];
-        stage_rows(0, rows);
-        load_rows(rows);
-        store_rows(0);
-        __syncthreads();
-        for (int st = 0; st < nstages; ++st) {
-            const bool more = st + 1 < nstages;
-            if (more) {
-                stage_rows(st + 1, rows);
-                load_rows(rows);
-            }
-            const unsigned char* kb = kvbuf + (st & 1) * kStageBytes;
-            const unsigned char* vb = kb + 2 * kKTile;
 #pragma unroll
-            for (int tt = 0; tt < 2; ++tt) {
-                const int t = 2 * st + tt;
-                if (t < ntiles) {
-                    if (GATHER) gather_tile(list + 32 * t, kb + tt * kKTile, vb + tt * kVTile);
-                    else block_tile(__builtin_amdgcn_readfirstlane(DENSE ? t : list[t]), kb + tt * kKTile, vb + tt * kVTile);
+        for (int st = 0; st < 2; ++st) {
+            if (st < nstages) {
+                stage_rows(st, rows);
+                load_stage(rows);
+                store_stage(st);
+            }
+        }
+        __syncthreads();
+        bf16x8 k0[8], k1[8], vf[8], p0[2], p1[2];
+        TileInfo a = info(0), b = info(1);
+        if (a.live) read_k(0, k0);
+        auto pv = [&](const bf16x8 (&pk)[2]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) oacc[j >> 1] = mfma32(vf[j], pk[j & 1], oacc[j >> 1]);
+        };
+        int buf = 0;                                         // buffer of stage st; st+1 is in buf+1, st+2 goes to buf+2 (mod 3)
+        for (int st = 0; st < nstages; ++st) {
+            if (st > 0) __syncthreads();
+            const int buf1 = buf == 2 ? 0 : buf + 1, buf2 = buf1 == 2 ? 0 : buf1 + 1;
+            // list / bitmap words of the next stage are requested before the staging loads: the memory counters retire
+            // in order, so waiting for them does not wait for the (younger) staging loads
+            const TileInfo na = info(2 * st + 2), nb = info(2 * st + 3);
+            const bool more = st + 2 < nstages;
+            if (more) {
+                stage_rows(st + 2, rows);
+                load_stage(rows);
+            }
+            f32x16 s0, s1;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) s0[e] = s1[e] = 0.f;
+            if (DENSE) {
+                // both tiles are live almost always: two independent accumulation chains, issued alternately
+                if (b.live) read_k(2 * buf + 1, k1);
+                if (a.live && b.live) {
+                    tiles_done += 2;
+#pragma unroll
+                    for (int kk = 0; kk < 8; ++kk) {
+                        s0 = mfma32(k0[kk], qf[kk], s0);
+                        s1 = mfma32(k1[kk], qf[kk], s1);
+                    }
+                } else if (a.live) {
+                    ++tiles_done;
+#pragma unroll
+                    for (int kk = 0; kk < 8; ++kk) s0 = mfma32(k0[kk], qf[kk], s0);
+                }
+            } else {
+                // one chain after the other: the second tile's fragments can reuse the registers of the first
+                if (a.live) {
+                    ++tiles_done;
+#pragma unroll
+                    for (int kk = 0; kk < 8; ++kk) s0 = mfma32(k0[kk], qf[kk], s0);
+                }
+                if (b.live) {
+                    ++tiles_done;
+                    read_k(2 * buf + 1, k1);
+#pragma unroll
+                    for (int kk = 0; kk < 8; ++kk) s1 = mfma32(k1[kk], qf[kk], s1);
                 }
             }
-            if (more) store_rows((st + 1) & 1);
-            __syncthreads();
+            if (na.live) read_k(2 * buf1, k0);               // first tile of the next stage: in LDS since the last barrier
+            if (a.live || b.live) {
+                float mx = NEG_INF;
+                if (a.live) {
+                    apply_mask(s0, a, gather_tag);
+                    mx = tile_max(s0);
+                }
+                if (b.live) {
+                    apply_mask(s1, b, gather_tag);
+                    mx = fmaxf(mx, tile_max(s1));
+                }
+                const float m_new = fmaxf(m_run, half_swap_max(mx));
+                if (__ballot((m_new - m_run) * p.c > kRescaleThreshold)) rescale(m_new);   // false when both are -inf
+                const float mc = (m_run == NEG_INF) ? 0.f : m_run * p.c;
+                float lsum = 0.f;
+                if (a.live) {
+                    exp_part(s0, 0, 16, mc, lsum);
+                    pack_p(s0, p0);
+                }
+                if (b.live) {
+                    exp_part(s1, 0, 16, mc, lsum);
+                    pack_p(s1, p1);
+                }
+                l_run += lsum;
+                if (a.live) {
+                    read_v(2 * buf, vf);
+                    pv(p0);
+                }
+                if (b.live) {
+                    read_v(2 * buf + 1, vf);
+                    pv(p1);
+                }
+            }
+            if (more) store_stage(buf2);
+            a = na;
+            b = nb;
+            buf = buf1;
         }
+        __syncthreads();                                     // the ring and the list are reused by the next phase
     };
 
     // ---- phases ----
@@ -413,15 +508,27 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
             }
         }
         __syncthreads();
-        // 2. slash part: marked blocks, in rounds of kListCap candidate blocks
-        for (int rbase = 0; rbase < nblk; rbase += kListCap) {
+        // 2. slash part: marked blocks in ascending order, in rounds of at most bcap listed blocks.  Each listed
+        //    block gets its column word and, per 32-row sub-block of the tile, its window of the offset bitmap:
+        //    all bitmap reads of the tile happen here, in parallel, not inside the attention loop.
+        const int chunk = min(kThreads, bcap);               // candidates per append: never more than a round can hold
+        for (int cbase = 0; cbase < nblk;) {
             int count = 0;
-            const int rend = min(nblk, rbase + kListCap);
-            for (int base = rbase; base < rend; base += kThreads) {
-                const int b = base + tid;
-                const bool flag = b < rend && ((tbits[b >> 5] >> (b & 31)) & 1u);
+            while (cbase < nblk && count + chunk <= bcap) {   // true at count == 0, so every round advances cbase
+                const int b = cbase + tid;
+                const bool flag = tid < chunk && b < nblk && ((tbits[b >> 5] >> (b & 31)) & 1u);
                 count = wg_append(flag, b, list, count, wtot);
+                cbase += chunk;
             }
+            for (int e = tid; e < count; e += kThreads) {
+                const int b = list[e];
+                list_vw[e] = vbit[b];
+                for (int r = 0; r < nsub; ++r) {
+                    const int dlt = i0 + 32 * r - 32 * b;
+                    list_w[r * bcap + e] = dlt < -31 ? 0ull : (window64(sbit, dlt + 33) & kAll63);
+                }
+            }
+            __syncthreads();
             run_phase(count, std::false_type{});
         }
         // 3. vertical part: causal columns outside the marked blocks, gathered row by row
