@@ -158,6 +158,8 @@ def main():
     ap.add_argument("--config", type=int, default=4, choices=[4, 5])
     ap.add_argument("--dense-reps", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain 1 GiB device copies (reference dispatches for scaling profiler byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the path shards by KV group with no exchange; "
@@ -189,6 +191,14 @@ def main():
     w.dense()
     torch.cuda.synchronize()
     t_dense = float(np.median(timed(w.dense, args.dense_reps)))
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     idx_v, cnt_v = w.idx_v.cpu().numpy(), w.cnt_v.cpu().numpy()
     idx_s, cnt_s = w.idx_s.cpu().numpy(), w.cnt_s.cpu().numpy()
