@@ -61,7 +61,7 @@ constexpr size_t kListVwOff = kListOff + kListCap * 4;
 constexpr size_t kListWOff = kListVwOff + (kListCap / 2) * 4;
 constexpr size_t kTbitOff = kListWOff + kListCap * 8;
 constexpr size_t kScratchOff = kTbitOff + kTbitWords * 4;
-constexpr size_t kSmemBytes = kScratchOff + 64;
+constexpr size_t kSmemBytes = kScratchOff + 128;
 constexpr uint64_t kAll63 = 0x7fffffffffffffffull;
 constexpr float kRescaleThreshold = 8.0f;      // log2 units: stale maxima up to 2^8 are tolerated
 
@@ -80,6 +80,8 @@ struct AttnParams {
     const uint32_t* vbit;           // per index head: bit j set iff column j selected
     const uint32_t* t32;            // per index head: bit t set iff an offset in [32t-31, 32t+31] is selected
     int sw, vw, tw;                 // words per head of the three bitmaps
+    const int32_t* ncol32;          // per index head and 32-row block q: number of listed columns <= 32 q + 31
+    int nq32;                       // entries per head of ncol32
     unsigned long long* tile_counter;
 };
 
@@ -135,22 +137,24 @@ __device__ __forceinline__ void mask_elements(f32x16& acc, uint64_t w, uint64_t 
     if constexpr (E + 1 < 16) mask_elements<E + 1>(acc, w, cz, vw, dead);
 }
 
-// Ordered append of the flagged threads' values to list[base...]; returns the new length.
-__device__ __forceinline__ int wg_append(bool flag, int value, int* list, int base, int* wtot) {
+// Ordered append of the flagged threads' values to list[base...]; returns the new length.  `parity` alternates
+// between calls so that one barrier per call is enough (the wave totals of call c+1 go to the other buffer while
+// slow wavefronts may still read those of call c).  The caller puts a barrier after its last call.
+__device__ __forceinline__ int wg_append(bool flag, int value, int* list, int base, int* wtot, int parity) {
     const uint64_t bal = __ballot(flag);
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int pre = __popcll(bal & ((1ull << lane) - 1ull));
-    if (lane == 0) wtot[w] = __popcll(bal);
+    int* tot_buf = wtot + parity * kWaves;
+    if (lane == 0) tot_buf[w] = __popcll(bal);
     __syncthreads();
     int off = base, tot = 0;
 #pragma unroll
     for (int i = 0; i < kWaves; ++i) {
-        const int c = wtot[i];
+        const int c = tot_buf[i];
         if (i < w) off += c;
         tot += c;
     }
     if (flag) list[off + pre] = value;
-    __syncthreads();
     return base + tot;
 }
 
@@ -514,12 +518,15 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
         const int chunk = min(kThreads, bcap);               // candidates per append: never more than a round can hold
         for (int cbase = 0; cbase < nblk;) {
             int count = 0;
+            int par = 0;
             while (cbase < nblk && count + chunk <= bcap) {   // true at count == 0, so every round advances cbase
                 const int b = cbase + tid;
                 const bool flag = tid < chunk && b < nblk && ((tbits[b >> 5] >> (b & 31)) & 1u);
-                count = wg_append(flag, b, list, count, wtot);
+                count = wg_append(flag, b, list, count, wtot, par);
+                par ^= 1;
                 cbase += chunk;
             }
+            __syncthreads();
             for (int e = tid; e < count; e += kThreads) {
                 const int b = list[e];
                 list_vw[e] = vbit[b];
@@ -533,25 +540,27 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
         }
         // 3. vertical part: causal columns outside the marked blocks, gathered row by row
         const int32_t* __restrict__ iv = p.idx_v + static_cast<size_t>(ih) * p.cap_v;
-        int ncand;
-        {
-            int lo = 0, hi = min(p.cnt_v[ih], p.cap_v);     // first entry > i_last
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                if (iv[mid] <= i_last) lo = mid + 1; else hi = mid;
-            }
-            ncand = lo;
-        }
+        // number of listed columns <= i_last: prepared per 32-row block (block_count_kernel)
+        const int ncand = p.ncol32[static_cast<size_t>(ih) * p.nq32 + (i_last >> 5)];
         int cursor = 0;
         while (cursor < ncand) {
-            int count = 0;
-            while (cursor < ncand && count + kThreads <= kListCap) {
-                const int t = cursor + tid;
-                const int col = t < ncand ? iv[t] : -1;
-                const bool flag = col >= 0 && !((tbits[col >> 10] >> ((col >> 5) & 31)) & 1u);
-                count = wg_append(flag, col, list, count, wtot);
-                cursor += kThreads;
+            int count = 0, par = 0;
+            while (cursor < ncand && count + 4 * kThreads <= kListCap) {
+                int col[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {                // one round trip to memory for four appends
+                    const int t = cursor + u * kThreads + tid;
+                    col[u] = t < ncand ? iv[t] : -1;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const bool flag = col[u] >= 0 && col[u] <= i_last && !((tbits[col[u] >> 10] >> ((col[u] >> 5) & 31)) & 1u);
+                    count = wg_append(flag, col[u], list, count, wtot, par);
+                    par ^= 1;
+                }
+                cursor += 4 * kThreads;
             }
+            __syncthreads();
             const int padded = (count + 63) & ~63;
             for (int t = count + tid; t < padded; t += kThreads) list[t] = INT_MAX;
             __syncthreads();
@@ -617,9 +626,24 @@ __global__ void block_diag_kernel(const uint32_t* sbit, int sw, uint32_t* t32, i
     }
 }
 
+// ncol32[ih][q] = number of entries of the ascending column list that are <= 32 q + 31 (and < n)
+__global__ void column_count_kernel(const int32_t* idx, const int32_t* cnt, int cap, int n, int32_t* ncol32, int nq32) {
+    const int ih = blockIdx.y;
+    const int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= nq32) return;
+    const int32_t* iv = idx + static_cast<size_t>(ih) * cap;
+    const int limit = min(32 * q + 31, n - 1);
+    int lo = 0, hi = min(cnt[ih], cap);
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (iv[mid] <= limit) lo = mid + 1; else hi = mid;
+    }
+    ncol32[static_cast<size_t>(ih) * nq32 + q] = lo;
+}
+
 struct SparseWs {
-    size_t counter_off, sbit_off, vbit_off, t32_off, total;
-    int sw, vw, tw;
+    size_t counter_off, sbit_off, vbit_off, t32_off, ncol_off, total;
+    int sw, vw, tw, nq32;
 };
 
 SparseWs sparse_ws_layout(int index_heads, int64_t n) {
@@ -632,7 +656,9 @@ SparseWs sparse_ws_layout(int index_heads, int64_t n) {
     w.sbit_off = 256;
     w.vbit_off = w.sbit_off + static_cast<size_t>(index_heads) * w.sw * 4;
     w.t32_off = w.vbit_off + static_cast<size_t>(index_heads) * w.vw * 4;
-    w.total = vs::round_up(w.t32_off + static_cast<size_t>(index_heads) * w.tw * 4, 256);
+    w.nq32 = static_cast<int>(nblk);
+    w.ncol_off = vs::round_up(w.t32_off + static_cast<size_t>(index_heads) * w.tw * 4, 256);
+    w.total = vs::round_up(w.ncol_off + static_cast<size_t>(index_heads) * w.nq32 * 4, 256);
     return w;
 }
 
@@ -710,6 +736,10 @@ int vs_sparse_prefill(const void* q, const void* k, const void* v, int q_heads, 
     hipLaunchKernelGGL(block_diag_kernel, dim3((w.tw * 32 + 255) / 256, index_heads), dim3(256), 0, st, sbit, w.sw, t32, w.tw,
                        nbits);
     VS_LAUNCH_CHECK();
+    int32_t* ncol32 = reinterpret_cast<int32_t*>(base + w.ncol_off);
+    hipLaunchKernelGGL(column_count_kernel, dim3((w.nq32 + 255) / 256, index_heads), dim3(256), 0, st, idx_v, cnt_v, cap_v,
+                       static_cast<int>(n), ncol32, w.nq32);
+    VS_LAUNCH_CHECK();
 
     AttnParams p{};
     p.q = static_cast<const uint16_t*>(q);
@@ -734,6 +764,8 @@ int vs_sparse_prefill(const void* q, const void* k, const void* v, int q_heads, 
     p.sw = w.sw;
     p.vw = w.vw;
     p.tw = w.tw;
+    p.ncol32 = ncol32;
+    p.nq32 = w.nq32;
     p.tile_counter = reinterpret_cast<unsigned long long*>(base + w.counter_off);
     return launch_attention<false>(p, st);
 }
