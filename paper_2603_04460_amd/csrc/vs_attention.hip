@@ -494,37 +494,72 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     if (DENSE) {
         run_phase(nblk, std::false_type{});
     } else {
-        // 1. blocks crossed by a selected diagonal for any 32-row sub-block of the tile
+        // 1. blocks crossed by a selected diagonal for any 32-row sub-block of the tile, one 32-block word per thread:
+        //    block b = 32 W + j is crossed by sub-block r iff T32 bit (qb0 + r - b) is set, so the word is the
+        //    bit-reversed 32-bit window of T32 that ends at qb0 + r - 32 W (bits below 0 do not exist).
         const int qb0 = i0 >> 5;
-        for (int base = 0; base < nblk; base += kThreads) {
-            const int b = base + tid;
-            bool touched = false;
-            if (b < nblk) {
-                for (int r = 0; r < nsub; ++r) {
-                    const int dl = qb0 + r - b;
-                    if (dl >= 0) touched |= (t32[dl >> 5] >> (dl & 31)) & 1u;
+        const int nwords = (nblk + 31) >> 5;
+        for (int W = tid; W < nwords; W += kThreads) {
+            uint32_t acc = 0;
+            for (int r = 0; r < nsub; ++r) {
+                const int top = qb0 + r - 32 * W;            // diagonal index of block 32 W (bit 0 of the word)
+                if (top < 0) continue;
+                const int start = top - 31;
+                uint32_t win;
+                if (start >= 0) {
+                    const uint64_t two = (static_cast<uint64_t>(t32[(start >> 5) + 1]) << 32) | t32[start >> 5];
+                    win = static_cast<uint32_t>(two >> (start & 31));
+                } else {
+                    win = t32[0] << (-start);
                 }
+                acc |= __builtin_bitreverse32(win);
             }
-            const uint64_t bal = __ballot(touched);
-            if (lane == 0) {
-                tbits[(base >> 5) + 2 * wave] = static_cast<uint32_t>(bal);
-                tbits[(base >> 5) + 2 * wave + 1] = static_cast<uint32_t>(bal >> 32);
-            }
+            const int valid = nblk - 32 * W;                 // blocks of this word that exist
+            if (valid < 32) acc &= (1u << valid) - 1u;
+            tbits[W] = acc;
         }
         __syncthreads();
-        // 2. slash part: marked blocks in ascending order, in rounds of at most bcap listed blocks.  Each listed
-        //    block gets its column word and, per 32-row sub-block of the tile, its window of the offset bitmap:
-        //    all bitmap reads of the tile happen here, in parallel, not inside the attention loop.
-        const int chunk = min(kThreads, bcap);               // candidates per append: never more than a round can hold
-        for (int cbase = 0; cbase < nblk;) {
-            int count = 0;
-            int par = 0;
-            while (cbase < nblk && count + chunk <= bcap) {   // true at count == 0, so every round advances cbase
-                const int b = cbase + tid;
-                const bool flag = tid < chunk && b < nblk && ((tbits[b >> 5] >> (b & 31)) & 1u);
-                count = wg_append(flag, b, list, count, wtot, par);
-                par ^= 1;
-                cbase += chunk;
+        // 2. slash part: marked blocks in ascending order.  Thread t owns words 2t and 2t+1 of the marks; an exclusive
+        //    scan of the popcounts gives every marked block its position, and blocks are listed in rounds of bcap
+        //    positions.  Each listed block gets its column word and, per 32-row sub-block of the tile, its window of
+        //    the offset bitmap: all bitmap reads of the tile happen here, in parallel, not inside the attention loop.
+        int nmarked;
+        int my_pos;                                          // position of this thread's first marked block
+        uint32_t my_bits[2];
+        {
+            my_bits[0] = 2 * tid < nwords ? tbits[2 * tid] : 0u;
+            my_bits[1] = 2 * tid + 1 < nwords ? tbits[2 * tid + 1] : 0u;
+            const int mine = __popc(my_bits[0]) + __popc(my_bits[1]);
+            int incl = mine;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int y = __shfl_up(incl, d);
+                if (lane >= d) incl += y;
+            }
+            if (lane == 63) wtot[wave] = incl;
+            __syncthreads();
+            int before = 0, total = 0;
+#pragma unroll
+            for (int i = 0; i < kWaves; ++i) {
+                const int c = wtot[i];
+                if (i < wave) before += c;
+                total += c;
+            }
+            my_pos = before + incl - mine;
+            nmarked = total;
+        }
+        for (int rbase = 0; rbase < nmarked; rbase += bcap) {
+            const int count = min(bcap, nmarked - rbase);
+            int pos = my_pos - rbase;
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                uint32_t bits = my_bits[u];
+                while (bits) {
+                    const int j = __builtin_ctz(bits);
+                    bits &= bits - 1u;
+                    if (pos >= 0 && pos < count) list[pos] = 32 * (2 * tid + u) + j;
+                    ++pos;
+                }
             }
             __syncthreads();
             for (int e = tid; e < count; e += kThreads) {
