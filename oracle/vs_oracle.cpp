@@ -279,17 +279,22 @@ int vso_select(const float* scores, int heads, int64_t n, int mode, double tau, 
 // Query head h reads KV head h / (q_heads / kv_heads); its index lists come from index head
 // h (index_heads == q_heads) or from its KV head (index_heads == kv_heads).
 // Kept set of row i: { j : 0 <= j <= i and ( j in I_v or i - j in I_s ) }, each key once.
+// granularity g > 1 selects the tile-granular slash variant: rows are grouped in blocks of g (row i belongs to
+// rows g*floor(i/g) .. g*floor(i/g)+g-1) and key j <= i is kept if it is a selected column or ANY row i' of the
+// block of i has i' - j in I_s.  g = 1 is the mask equation itself.
 // rows: optional list of row numbers (n_rows of them); NULL -> all n rows in order.
 // out: [q_heads, n_rows, d] fp64; lse: [q_heads, n_rows] or NULL; live: [q_heads, n_rows] or NULL.
 int vso_sparse_attention(const uint16_t* q, const uint16_t* k, const uint16_t* v,
                          int q_heads, int kv_heads, int64_t n, int d, double scale,
                          const int32_t* idx_v, const int32_t* cnt_v, int64_t cap_v,
                          const int32_t* idx_s, const int32_t* cnt_s, int64_t cap_s, int index_heads,
+                         int64_t granularity,
                          const int64_t* rows, int64_t n_rows,
                          double* out, double* lse, int64_t* live, int threads) {
     if (!q || !k || !v || !idx_v || !cnt_v || !idx_s || !cnt_s || !out) return -1;
     if (q_heads <= 0 || kv_heads <= 0 || q_heads % kv_heads || n <= 0 || d <= 0) return -1;
     if (index_heads != q_heads && index_heads != kv_heads) return -1;
+    if (granularity < 1) return -1;
     if (!rows) n_rows = n;
     const int group = q_heads / kv_heads;
     // membership tables per index head
@@ -317,7 +322,13 @@ int vso_sparse_attention(const uint16_t* q, const uint16_t* k, const uint16_t* v
         double l;
         int64_t c = attention_row(q + (static_cast<int64_t>(h) * n + i) * d, k + static_cast<int64_t>(g) * n * d,
                                   v + static_cast<int64_t>(g) * n * d, i, d, scale,
-                                  [&](int64_t j) { return cv[j] || cs[i - j]; },
+                                  [&](int64_t j) {
+                                      if (cv[j]) return true;
+                                      const int64_t first = granularity * (i / granularity);
+                                      for (int64_t r = first; r < first + granularity && r < n; ++r)
+                                          if (r - j >= 0 && cs[r - j]) return true;
+                                      return false;
+                                  },
                                   out + item * d, &l);
         if (lse) lse[item] = l;
         if (live) live[item] = c;

@@ -122,9 +122,11 @@ def _lists(idx, cnt):
     return idx, cnt
 
 
-def sparse_attention(q, k, v, idx_v, cnt_v, idx_s, cnt_s, scale=None, rows=None, threads=0, return_live=False):
+def sparse_attention(q, k, v, idx_v, cnt_v, idx_s, cnt_s, scale=None, rows=None, threads=0, return_live=False,
+                     granularity=1):
     """q: [Hq, n, d], k, v: [Hkv, n, d] uint16.  idx_*: [index_heads, cap] int32 ascending, cnt_*: [index_heads].
-    Returns (out [Hq, n_rows, d] f64, lse [Hq, n_rows] f64[, live [Hq, n_rows] int64])."""
+    granularity g > 1: tile-granular slash variant (a key is kept for a row if any row of its g-row block reaches it
+    through a selected offset).  Returns (out [Hq, n_rows, d] f64, lse [Hq, n_rows] f64[, live [Hq, n_rows] int64])."""
     L = _load()
     q = _c(q, np.uint16); k = _c(k, np.uint16); v = _c(v, np.uint16)
     hq, n, d = q.shape
@@ -141,7 +143,7 @@ def sparse_attention(q, k, v, idx_v, cnt_v, idx_s, cnt_s, scale=None, rows=None,
                                 ctypes.c_int(d), ctypes.c_double(scale),
                                 _p(idx_v), _p(cnt_v), ctypes.c_int64(idx_v.shape[1]),
                                 _p(idx_s), _p(cnt_s), ctypes.c_int64(idx_s.shape[1]), ctypes.c_int(ih),
-                                _p(rows_a), ctypes.c_int64(nr), _p(out), _p(lse), _p(live), ctypes.c_int(threads))
+                                ctypes.c_int64(granularity), _p(rows_a), ctypes.c_int64(nr), _p(out), _p(lse), _p(live), ctypes.c_int(threads))
     if rc != 0:
         raise ValueError("vso_sparse_attention rc=%d" % rc)
     return (out, lse, live) if return_live else (out, lse)

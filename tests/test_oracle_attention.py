@@ -243,3 +243,53 @@ def test_vs_aggregate_and_recall():
     np.testing.assert_allclose(rec, (A * keep).sum() / n, atol=1e-13)
     _, _, rec_full = oracle.vs_aggregate(q, k, idx_v=[], idx_s=list(range(n)))
     np.testing.assert_allclose(rec_full, 1.0, atol=1e-13)
+
+
+def _granular_mask(n, I_v, I_s, g):
+    """The tile-granular kept set written directly from its definition (numpy, no oracle code)."""
+    I_v, I_s = set(int(x) for x in I_v), set(int(x) for x in I_s)
+    M = np.full((n, n), -np.inf)
+    for i in range(n):
+        first = g * (i // g)
+        for j in range(i + 1):
+            if j in I_v or any((r - j) in I_s for r in range(first, min(first + g, n)) if r - j >= 0):
+                M[i, j] = 0.0
+    return M
+
+
+def test_tile_granular_hand_worked_example():
+    n, I_v, I_s, rows = _read_gold("vs_mask_n8_g4.txt")
+    d = 4
+    q = np.zeros((1, n, d), dtype=np.uint16)
+    k = rand_bits(np.random.default_rng(1), 1, n, d)
+    vf = (np.arange(n)[:, None] + np.array([0.0, 16.0, 32.0, 64.0])[None, :]).astype(np.float32)
+    v = f32_to_bf16_bits(vf)[None]
+    iv, cv = lists(I_v)
+    is_, cs = lists(I_s)
+    out, lse, live = oracle.sparse_attention(q, k, v, iv, cv, is_, cs, return_live=True, granularity=4)
+    assert int(live.sum()) == 36
+    for i in range(n):
+        assert live[0, i] == len(rows[i]) == i + 1
+        np.testing.assert_allclose(out[0, i], vf[rows[i]].astype(np.float64).mean(axis=0), atol=1e-12)
+    dense, _ = oracle.dense_attention(q, k, v)
+    np.testing.assert_allclose(out, dense, atol=1e-13)
+
+
+@pytest.mark.parametrize("n,g,seed", [(24, 4, 0), (40, 8, 1), (70, 32, 2), (33, 32, 3), (16, 1, 4)])
+def test_tile_granular_matches_definition_and_contains_exact(n, g, seed):
+    rng = np.random.default_rng(seed)
+    d = 8
+    q, k, v = rand_bits(rng, 2, n, d), rand_bits(rng, 1, n, d), rand_bits(rng, 1, n, d)
+    sv = rng.choice(n, size=3, replace=False)
+    ss = np.concatenate([[0], rng.choice(np.arange(1, n), size=4, replace=False)])
+    iv, cv = lists(sv)
+    is_, cs = lists(ss)
+    out, lse, live = oracle.sparse_attention(q, k, v, iv, cv, is_, cs, return_live=True, granularity=g)
+    M = _granular_mask(n, sv, ss, g)
+    for h in range(2):
+        ref, _ = masked_attention(bits_to_f64(q[h]), bits_to_f64(k[0]), bits_to_f64(v[0]), M, 1 / np.sqrt(d))
+        np.testing.assert_allclose(out[h], ref, atol=1e-12)
+    exact = np.isfinite(vs_mask(n, sv, ss))
+    assert np.all(np.isfinite(M)[exact])                     # superset of the element-exact mask
+    if g == 1:
+        assert np.array_equal(np.isfinite(M), exact)
