@@ -144,6 +144,19 @@ int vs_sparse_prefill(const void* q, const void* k, const void* v, int q_heads, 
                       void* o_bf16, float* lse, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Tile-granular slash variant of vs_sparse_prefill (Sec. "Fused attention kernel implementation": the merged index
+ * set is built per query block).  slash_granularity g groups the query rows in aligned blocks of g rows; row i keeps
+ *     { j : 0 <= j <= i  and  ( j in I_v  or  i' - j in I_s for SOME row i' of the block of i ) },
+ * a superset of the element-exact mask (g = 1, identical to vs_sparse_prefill).  Supported: g = 1 and g = 32.
+ * All other arguments, the workspace and the error behaviour are those of vs_sparse_prefill; an unsupported g
+ * returns VS_ERR_UNSUPPORTED.
+ */
+int vs_sparse_prefill_tiled(const void* q, const void* k, const void* v, int q_heads, int kv_heads, int64_t n,
+                            float scale, const int32_t* idx_v, const int32_t* cnt_v, int cap_v,
+                            const int32_t* idx_s, const int32_t* cnt_s, int cap_s, int index_heads,
+                            int slash_granularity, void* o_bf16, float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Dense causal attention on the same layout (Sec. "Attention Computation", Eqs. P, A, O, with
  * j <= i): the in-library full-attention baseline.  Same kernel pipeline as the sparse call.
  */

@@ -12,7 +12,8 @@ _lib = None
 
 EXPORTS = [
     "vs_rope_apply", "vs_index_score_workspace", "vs_index_score", "vs_select_budget_workspace", "vs_select_budget",
-    "vs_sparse_prefill_workspace", "vs_sparse_prefill", "vs_dense_prefill", "vs_sparse_prefill_tiles",
+    "vs_sparse_prefill_workspace", "vs_sparse_prefill", "vs_sparse_prefill_tiled", "vs_dense_prefill",
+    "vs_sparse_prefill_tiles",
     "vs_strerror", "vs_last_hip_error", "vs_version",
 ]
 
@@ -61,6 +62,7 @@ def _load():
     L.vs_sparse_prefill_workspace.argtypes = [i32, i32, i32, i64]
     L.vs_sparse_prefill_workspace.restype = sz
     L.vs_sparse_prefill.argtypes = [vp, vp, vp, i32, i32, i64, f32, vp, vp, i32, vp, vp, i32, i32, vp, vp, vp, sz, vp]
+    L.vs_sparse_prefill_tiled.argtypes = [vp, vp, vp, i32, i32, i64, f32, vp, vp, i32, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
     L.vs_dense_prefill.argtypes = [vp, vp, vp, i32, i32, i64, f32, vp, vp, vp]
     L.vs_sparse_prefill_tiles.argtypes = [vp, sz, vp, ctypes.POINTER(ctypes.c_int64)]
     L.vs_strerror.argtypes = [i32]
@@ -182,7 +184,7 @@ def sparse_prefill_workspace(q_heads, kv_heads, index_heads, n):
     return _load().vs_sparse_prefill_workspace(q_heads, kv_heads, index_heads, n)
 
 
-def sparse_prefill(q, k, v, idx_v, cnt_v, idx_s, cnt_s, o, lse, ws, scale=None, stream=None):
+def sparse_prefill(q, k, v, idx_v, cnt_v, idx_s, cnt_s, o, lse, ws, scale=None, stream=None, slash_granularity=None):
     import torch
     _dev(q, torch.bfloat16, "q"); _dev(k, torch.bfloat16, "k"); _dev(v, torch.bfloat16, "v"); _dev(o, torch.bfloat16, "o")
     _dev(idx_v, torch.int32, "idx_v"); _dev(idx_s, torch.int32, "idx_s")
@@ -196,10 +198,16 @@ def sparse_prefill(q, k, v, idx_v, cnt_v, idx_s, cnt_s, o, lse, ws, scale=None, 
         _dev(lse, torch.float32, "lse")
         assert lse.shape == (q_heads, n)
     scale = 128 ** -0.5 if scale is None else scale
-    _check(_load().vs_sparse_prefill(_ptr(q), _ptr(k), _ptr(v), q_heads, kv_heads, n, scale, _ptr(idx_v), _ptr(cnt_v),
-                                     idx_v.shape[1], _ptr(idx_s), _ptr(cnt_s), idx_s.shape[1], index_heads,
-                                     _ptr(o), _ptr(lse), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
-                                     _stream(stream)), "vs_sparse_prefill")
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    if slash_granularity is None:
+        _check(_load().vs_sparse_prefill(_ptr(q), _ptr(k), _ptr(v), q_heads, kv_heads, n, scale, _ptr(idx_v), _ptr(cnt_v),
+                                         idx_v.shape[1], _ptr(idx_s), _ptr(cnt_s), idx_s.shape[1], index_heads,
+                                         _ptr(o), _ptr(lse), _ptr(ws), ws_bytes, _stream(stream)), "vs_sparse_prefill")
+    else:
+        _check(_load().vs_sparse_prefill_tiled(_ptr(q), _ptr(k), _ptr(v), q_heads, kv_heads, n, scale, _ptr(idx_v),
+                                               _ptr(cnt_v), idx_v.shape[1], _ptr(idx_s), _ptr(cnt_s), idx_s.shape[1],
+                                               index_heads, int(slash_granularity), _ptr(o), _ptr(lse), _ptr(ws), ws_bytes,
+                                               _stream(stream)), "vs_sparse_prefill_tiled")
     return o
 
 

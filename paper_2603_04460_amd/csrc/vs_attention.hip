@@ -72,6 +72,7 @@ struct AttnParams {
     uint16_t* o;
     float* lse;
     int q_heads, kv_heads, group, hc, n, tiles, index_per_q;
+    int gran;                       // slash granularity: 1 (element-exact) or 32 (per 32-row block)
     float scale, c;                 // c = scale * log2(e)
     const int32_t* idx_v;
     const int32_t* cnt_v;
@@ -329,6 +330,26 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
         // selected offsets dlt-31 .. dlt+31 at bits 0..62 and the block's column word, both prepared with the list
         ti.w = DENSE ? ti.cz : uniform64(list_w[my_sub * bcap + t]);
         ti.vw = DENSE ? 0u : static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(list_vw[t]));
+        if (!DENSE && p.gran == 32) {
+            // Tile-granular slash: key kj is kept for every causal row of this 32-row block if ANY of its rows reaches it
+            // through a selected offset, i.e. if the window has a bit in [31 - kj, 62 - kj].  That is exactly how a
+            // selected column behaves inside the tile, so the keys join the column word and the offset window is dropped.
+            // x bit s = OR of window bits s .. s+len-1, len = rows of this block that exist (32 except at the end of
+            // the sequence): doubling up to the largest power of two pw <= len, then two overlapping windows
+            const int len = min(32, n - my_i0);
+            uint64_t x = ti.w;
+            int pw = 1;
+            while (2 * pw <= len) {
+                x |= x >> pw;
+                pw *= 2;
+            }
+            x |= x >> (len - pw);
+            ti.vw |= __builtin_bitreverse32(static_cast<uint32_t>(x));
+            ti.w = 0ull;
+            ti.live = ti.vw != 0u && ti.cz != 0ull;
+            ti.need = !(ti.vw == 0xffffffffu && ti.cz == kAll63);
+            return ti;
+        }
         ti.live = (ti.w | (ti.vw ? ti.cz : 0ull)) != 0ull;
         ti.need = ti.w != kAll63;
         return ti;
@@ -744,8 +765,17 @@ size_t vs_sparse_prefill_workspace(int q_heads, int kv_heads, int index_heads, i
 int vs_sparse_prefill(const void* q, const void* k, const void* v, int q_heads, int kv_heads, int64_t n, float scale,
                       const int32_t* idx_v, const int32_t* cnt_v, int cap_v, const int32_t* idx_s, const int32_t* cnt_s,
                       int cap_s, int index_heads, void* o_bf16, float* lse, void* ws, size_t ws_bytes, void* stream) {
+    return vs_sparse_prefill_tiled(q, k, v, q_heads, kv_heads, n, scale, idx_v, cnt_v, cap_v, idx_s, cnt_s, cap_s, index_heads,
+                                   1, o_bf16, lse, ws, ws_bytes, stream);
+}
+
+int vs_sparse_prefill_tiled(const void* q, const void* k, const void* v, int q_heads, int kv_heads, int64_t n, float scale,
+                            const int32_t* idx_v, const int32_t* cnt_v, int cap_v, const int32_t* idx_s,
+                            const int32_t* cnt_s, int cap_s, int index_heads, int slash_granularity, void* o_bf16,
+                            float* lse, void* ws, size_t ws_bytes, void* stream) {
     int rc = check_qkv(q, k, v, q_heads, kv_heads, n, scale, o_bf16);
     if (rc != VS_OK) return rc;
+    if (slash_granularity != 1 && slash_granularity != 32) return VS_ERR_UNSUPPORTED;
     if (!idx_v || !cnt_v || !idx_s || !cnt_s || cap_v <= 0 || cap_s <= 0) return VS_ERR_INVALID_ARG;
     if (index_heads != q_heads && index_heads != kv_heads) return VS_ERR_INVALID_ARG;
     const SparseWs w = sparse_ws_layout(index_heads, n);
@@ -787,6 +817,7 @@ int vs_sparse_prefill(const void* q, const void* k, const void* v, int q_heads, 
     p.group = q_heads / kv_heads;
     p.index_per_q = (index_heads == q_heads && q_heads != kv_heads) ? 1 : 0;
     p.hc = heads_per_workgroup(p.group, p.index_per_q != 0);
+    p.gran = slash_granularity;
     p.n = static_cast<int>(n);
     p.scale = scale;
     p.c = scale * 1.4426950408889634f;

@@ -29,7 +29,7 @@ def make_qkv(seed, hq, hkv, n, theta=1e6, local=False, rope=True):
     return (q, k, v), (synth.to_bits(q), synth.to_bits(k), synth.to_bits(v))
 
 
-def run_sparse(q, k, v, idx_v, cnt_v, idx_s, cnt_s, want_lse=True):
+def run_sparse(q, k, v, idx_v, cnt_v, idx_s, cnt_s, want_lse=True, granularity=None):
     hq, n, _ = q.shape
     hk = k.shape[0]
     iv = torch.from_numpy(np.ascontiguousarray(idx_v, dtype=np.int32)).cuda()
@@ -39,7 +39,7 @@ def run_sparse(q, k, v, idx_v, cnt_v, idx_s, cnt_s, want_lse=True):
     ws = torch.empty(vs.sparse_prefill_workspace(hq, hk, iv.shape[0], n), dtype=torch.uint8, device="cuda")
     o = torch.full_like(q, float("nan"))
     lse = torch.full((hq, n), float("nan"), dtype=torch.float32, device="cuda") if want_lse else None
-    vs.sparse_prefill(q, k, v, iv, cv, is_, cs, o, lse, ws)
+    vs.sparse_prefill(q, k, v, iv, cv, is_, cs, o, lse, ws, slash_granularity=granularity)
     tiles = vs.sparse_prefill_tiles(ws)
     torch.cuda.synchronize()
     return o, lse, tiles

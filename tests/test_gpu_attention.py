@@ -142,3 +142,25 @@ def test_argument_errors():
     with pytest.raises(vs.VsError) as e:
         vs.dense_prefill(q, k, v, o, scale=-1.0)
     assert e.value.code == -1
+
+
+@pytest.mark.parametrize("hq,hk,n,nv,ns", [(8, 2, 1500, 100, 200), (4, 1, 777, 30, 40), (4, 4, 640, 20, 60), (4, 1, 33, 2, 3)])
+def test_tile_granular_slash_mode(hq, hk, n, nv, ns):
+    """vs_sparse_prefill_tiled with g = 32 against the oracle's tile-granular mask; g = 1 equals vs_sparse_prefill."""
+    rng = np.random.default_rng(n + 1)
+    (q, k, v), (qb, kb, vb) = make_qkv(300 + n, hq, hk, n)
+    sv, ss = _random_sets(rng, n, hk, nv, ns)
+    iv, cv = lists(sv)
+    is_, cs = lists(ss)
+    o, lse, tiles = run_sparse(q, k, v, iv, cv, is_, cs, granularity=32)
+    ref_o, ref_lse, live = oracle.sparse_attention(qb, kb, vb, iv, cv, is_, cs, return_live=True, granularity=32)
+    check_attention(o, lse, ref_o, ref_lse)
+    assert tiles * 1024 >= live.sum()
+    o1, lse1, _ = run_sparse(q, k, v, iv, cv, is_, cs, granularity=1)
+    o0, lse0, _ = run_sparse(q, k, v, iv, cv, is_, cs)
+    assert torch.equal(o1.view(torch.int16), o0.view(torch.int16)) and torch.equal(lse1, lse0)
+    ws = torch.empty(vs.sparse_prefill_workspace(hq, hk, hk, n), dtype=torch.uint8, device="cuda")
+    with pytest.raises(vs.VsError) as e:
+        vs.sparse_prefill(q, k, v, torch.from_numpy(iv).cuda(), torch.from_numpy(cv).cuda(), torch.from_numpy(is_).cuda(),
+                          torch.from_numpy(cs).cuda(), o, None, ws, slash_granularity=16)
+    assert e.value.code == -2
