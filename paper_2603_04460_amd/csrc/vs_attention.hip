@@ -423,7 +423,9 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
         if (a.live) read_k(0, k0);
         auto pv = [&](const bf16x8 (&pk)[2]) __attribute__((always_inline)) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) oacc[j >> 1] = mfma32(vf[j], pk[j & 1], oacc[j >> 1]);
+            for (int t = 0; t < 2; ++t)                      // the four d-blocks in turn: consecutive MFMAs are independent
+#pragma unroll
+                for (int db = 0; db < 4; ++db) oacc[db] = mfma32(vf[2 * db + t], pk[t], oacc[db]);
         };
         int buf = 0;                                         // buffer of stage st; st+1 is in buf+1, st+2 goes to buf+2 (mod 3)
         for (int st = 0; st < nstages; ++st) {
