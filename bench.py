@@ -125,7 +125,7 @@ def cpu_baseline(w, idx_v, cnt_v, idx_s, cnt_s, pairs_total, dense_flop):
     n = w.n
     cores = os.cpu_count() or 1
     kb, vb = synth.to_bits(w.k[:1]), synth.to_bits(w.v[:1])
-    n_idx = min(n, 16384)
+    n_idx = min(n, 65536)
     t0 = time.time()
     oracle.index_score(kb[:, :n_idx], vb[:, :n_idx], *w.W_host, act=1)
     t_idx = (time.time() - t0) * (n / n_idx) * w.hk
@@ -135,7 +135,7 @@ def cpu_baseline(w, idx_v, cnt_v, idx_s, cnt_s, pairs_total, dense_flop):
     t_sel = (time.time() - t0) * 2 * w.hk
     group = w.hq // w.hk
     qb = synth.to_bits(w.q[:group])
-    rows = synth.sample_rows(1, n, 16, 16, 32)
+    rows = synth.sample_rows(1, n, 128, 128, 768)
     t0 = time.time()
     _, _, live = oracle.sparse_attention(qb, kb, vb, idx_v[:1], cnt_v[:1], idx_s[:1], cnt_s[:1], rows=rows, return_live=True)
     t_att_sample = time.time() - t0
@@ -145,7 +145,57 @@ def cpu_baseline(w, idx_v, cnt_v, idx_s, cnt_s, pairs_total, dense_flop):
             "sample": "indexer: 1 KV head x %d tokens (scaled to %d heads x %d); select: 1 head, 1 direction (x%d); "
                       "attention: %d sampled rows x %d query heads of KV group 0, %.2fs, extrapolated by live pairs"
                       % (n_idx, w.hk, n, 2 * w.hk, len(rows), group, t_att_sample),
-            "seconds_per_layer_extrapolated": total}
+            "seconds_per_layer_extrapolated": total,
+            "seconds_by_stage_extrapolated": {"indexer": t_idx, "select": t_sel, "attention": t_att}}
+
+
+def sweep(w, args, t_dense, dense_flop, dense_tiles, causal_pairs):
+    """Extra measurements around the default point (same resident tensors)."""
+    n, hq = w.n, w.hq
+    res = {"tau": {}}
+    for tau in (0.85, 0.9, 0.95):
+        w.budget.tau_v = w.budget.tau_s = tau
+        w.step()
+        torch.cuda.synchronize()
+        ms = float(np.median(timed(w.step, 5)))
+        t_att = float(np.median(timed(w.attention, 5)))
+        tiles = vs.sparse_prefill_tiles(w.ws_att)
+        iv, cv, is_, cs = w.idx_v.cpu().numpy(), w.cnt_v.cpu().numpy(), w.idx_s.cpu().numpy(), w.cnt_s.cpu().numpy()
+        pairs = live_pairs(iv, cv, is_, cs, n, hq // w.hk)
+        res["tau"]["%.2f" % tau] = {"ms_per_layer": ms, "attention_ms": t_att, "speedup_vs_dense": t_dense / ms,
+                                    "budget_fraction": pairs / causal_pairs, "tile_coverage": tiles / dense_tiles,
+                                    "executed_tile_tflops": tiles * FLOP_PER_TILE / (t_att * 1e-3) / 1e12,
+                                    "mfma_frac": tiles * FLOP_PER_TILE / (t_att * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                                    "k_v_mean": float(cv.mean()), "k_s_mean": float(cs.mean())}
+    w.budget.tau_v = w.budget.tau_s = args.tau
+    w.select()
+    # tile-granular slash mode (g = 32) on the default selection
+    f = lambda: vs.sparse_prefill(w.q, w.k, w.v, w.idx_v, w.cnt_v, w.idx_s, w.cnt_s, w.o, None, w.ws_att, slash_granularity=32)
+    f()
+    t = float(np.median(timed(f, 5)))
+    res["tile_granular_g32"] = {"attention_ms": t, "executed_tiles": vs.sparse_prefill_tiles(w.ws_att)}
+    # paper-shaped indexer: SiLU, hidden width 1024
+    W = synth.indexer_weights(synth.config_seed(args.config) + 100, 1024, 0)
+    wp = vs.IndexerWeights(*[torch.from_numpy(x).cuda() for x in W], 0.0, 0.0, 0)
+    ws = torch.empty(vs.index_score_workspace(w.hk, n, 1024), dtype=torch.uint8, device="cuda")
+    a1, a2 = torch.empty_like(w.a_v), torch.empty_like(w.a_s)
+    g = lambda: vs.index_score(w.k, w.v, wp, a1, a2, ws)
+    g()
+    t = float(np.median(timed(g, 5)))
+    res["indexer_silu_1024"] = {"ms": t, "mfma_tflops": 2.0 * 2 * 256 * 1024 * w.hk * n / (t * 1e-3) / 1e12}
+    # 36 layers, seeded tau per layer (whole-prefill attention path of a 36-layer model at this length)
+    taus = np.random.default_rng(synth.config_seed(args.config)).uniform(0.8, 0.95, size=36)
+    def layers():
+        for tau in taus:
+            w.budget.tau_v = w.budget.tau_s = float(tau)
+            w.step()
+    layers()
+    torch.cuda.synchronize()
+    t = float(np.median(timed(layers, 2)))
+    res["layers36"] = {"total_ms": t, "dense_total_ms": 36 * t_dense, "speedup_vs_dense": 36 * t_dense / t,
+                       "tau_min": float(taus.min()), "tau_max": float(taus.max())}
+    w.budget.tau_v = w.budget.tau_s = args.tau
+    return res
 
 
 def main():
@@ -158,6 +208,9 @@ def main():
     ap.add_argument("--config", type=int, default=4, choices=[4, 5])
     ap.add_argument("--dense-reps", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also time tau in {0.85, 0.9, 0.95}, the tile-granular slash mode, the paper-shaped indexer (SiLU, 1024) "
+                         "and a 36-layer pass with a seeded tau per layer in [0.8, 0.95] (same tensors for every layer)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (reference dispatches for scaling profiler byte counters)")
     args = ap.parse_args()
@@ -236,6 +289,8 @@ def main():
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, idx_v, cnt_v, idx_s, cnt_s, pairs, dense_flop)
+    if args.sweep:
+        out["sweep"] = sweep(w, args, t_dense, dense_flop, dense_tiles, causal_pairs)
     print(json.dumps(out))
 
 

@@ -24,9 +24,16 @@
 //      runs online-softmax attention on them.  The exact element mask
 //          live(i, j) = j <= i and ( offset i-j selected  or  column j selected )
 //      is a 63-bit window of the offset bitmap per 32x32 tile plus a 32-bit column word, both
-//      wave-uniform (SGPRs); they are turned into one 64-bit lane mask per accumulator element on the
-//      scalar unit, so masking costs one v_cndmask per element.  Interior tiles whose window is all
-//      ones skip the mask, row blocks whose window is empty skip the tile.
+//      wave-uniform (SGPRs).  Each lane shifts the window by its own query row, which leaves the
+//      keep-bits of its 16 accumulator elements in one register (four vector instructions per tile);
+//      an element then costs a bit-field extract and a bitwise select.  Interior tiles whose window
+//      is all ones skip the mask, row blocks whose window is empty skip the tile.
+//
+// Staging: global loads of a stage go to registers and from there to LDS.  The sparse kernel keeps two
+// register sets and issues the loads of stage s+3 while stage s is computed (they are written to LDS one
+// step later), so a load has a full step to arrive; the dense kernel, which has no registers to spare,
+// loads one step ahead.  Loads are never predicated: a predicated load would make the number of loads in
+// flight path-dependent and force a full wait before every LDS write.
 #include <hip/hip_runtime.h>
 #include <limits.h>
 #include <math.h>
@@ -43,6 +50,7 @@ typedef __bf16 bf16x4t __attribute__((__vector_size__(4 * sizeof(__bf16))));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kD = 128;
 constexpr int kThreads = 512;
@@ -114,28 +122,30 @@ __device__ __forceinline__ uint64_t uniform64(uint64_t x) {
     return (static_cast<uint64_t>(hi) << 32) | lo;
 }
 
-// val where the wave-uniform 64-bit lane mask has this lane's bit set, else dead
-__device__ __forceinline__ float keep_lanes(uint64_t lanemask, float val, float dead) {
-    float out;
-    asm("v_cndmask_b32_e64 %0, %1, %2, %3" : "=v"(out) : "v"(dead), "v"(val), "s"(lanemask));
-    return out;
+// Keep-bits of one lane of a 32x32 S^T tile.  Lane (q, h) holds, in accumulator element E = 4a + c, key kj = 8a + 4h + c
+// of query q; the result has that element's keep-bit at position 27 - 8a - c.
+// w: selected offsets dlt-31 .. dlt+31 at bits 0..62 (key kj of row q is offset bit 31 + q - kj); cz: the causal ones
+// among them; vw: selected columns of the block.  sh = q + 4 - 4h and ysh = 4 - 4h are per-lane constants.
+__device__ __forceinline__ uint32_t lane_keep_bits(uint64_t w, uint64_t cz, uint32_t vw, int sh, int ysh) {
+    const uint32_t x = static_cast<uint32_t>(w >> sh), cx = static_cast<uint32_t>(cz >> sh);
+    const uint32_t y = __builtin_bitreverse32(vw) >> ysh;   // bit 27 - 8a - c = column 8a + 4h + c
+    return x | (y & cx);
 }
 
-// Lane mask of accumulator element E of a 32x32 S^T tile: lane (q, h) holds key 8 (E/4) + 4 h + E%4 of query q.
-// w: selected offsets dlt-31 .. dlt+31 at bits 0..62; cz: the causal ones among them; vw: selected columns.
-template <int E>
-__device__ __forceinline__ uint64_t element_lanes(uint64_t w, uint64_t cz, uint32_t vw) {
-    constexpr int kj0 = 8 * (E >> 2) + (E & 3);
-    uint32_t lo = static_cast<uint32_t>(w >> (31 - kj0)), hi = static_cast<uint32_t>(w >> (27 - kj0));
-    if ((vw >> kj0) & 1u) lo |= static_cast<uint32_t>(cz >> (31 - kj0));
-    if ((vw >> (kj0 + 4)) & 1u) hi |= static_cast<uint32_t>(cz >> (27 - kj0));
-    return (static_cast<uint64_t>(hi) << 32) | lo;
-}
-
-template <int E>
-__device__ __forceinline__ void mask_elements(f32x16& acc, uint64_t w, uint64_t cz, uint32_t vw, float dead) {
-    acc[E] = keep_lanes(element_lanes<E>(w, cz, vw), acc[E], dead);
-    if constexpr (E + 1 < 16) mask_elements<E + 1>(acc, w, cz, vw, dead);
+// Four elements (one group a) at a time: the keep-bits spread over a word each (written out: from the C form the compiler
+// makes and + compare + select), then a bitwise select that stays visible to the compiler, which must space it from the
+// matrix instruction that produced acc.
+template <int A>
+__device__ __forceinline__ void mask_elements(f32x16& acc, uint32_t keep, uint32_t dead_bits) {
+    uint32_t m0, m1, m2, m3;
+    asm("v_bfe_i32 %0, %4, %5, 1\n\tv_bfe_i32 %1, %4, %6, 1\n\tv_bfe_i32 %2, %4, %7, 1\n\tv_bfe_i32 %3, %4, %8, 1"
+        : "=&v"(m0), "=&v"(m1), "=&v"(m2), "=&v"(m3)
+        : "v"(keep), "n"(27 - 8 * A), "n"(26 - 8 * A), "n"(25 - 8 * A), "n"(24 - 8 * A));
+    acc[4 * A] = __uint_as_float((m0 & __float_as_uint(acc[4 * A])) | (~m0 & dead_bits));
+    acc[4 * A + 1] = __uint_as_float((m1 & __float_as_uint(acc[4 * A + 1])) | (~m1 & dead_bits));
+    acc[4 * A + 2] = __uint_as_float((m2 & __float_as_uint(acc[4 * A + 2])) | (~m2 & dead_bits));
+    acc[4 * A + 3] = __uint_as_float((m3 & __float_as_uint(acc[4 * A + 3])) | (~m3 & dead_bits));
+    if constexpr (A + 1 < 4) mask_elements<A + 1>(acc, keep, dead_bits);
 }
 
 // Ordered append of the flagged threads' values to list[base...]; returns the new length.  `parity` alternates
@@ -226,26 +236,30 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
 
     // ---- staging: a stage is two 32-key tiles; thread moves 16-byte chunk (tid & 15) of row (tid >> 4) of K and V of each ----
     const int st_row = tid >> 4, st_chunk = tid & 15;
-    uint4 kreg[2], vreg[2];
-    auto load_stage = [&](const int (&rows)[2]) __attribute__((always_inline)) {
+    // two register sets: the global loads of stage st+3 are issued at the top of step st and written to LDS at the end
+    // of step st+1, so a load has two steps to arrive
+    u32x4 kreg[2][2], vreg[2][2];
+    // the dense kernel has no registers to spare for a second set: it loads one step ahead
+    constexpr bool kDeep = !DENSE;
+    constexpr std::integral_constant<int, 0> set0{};
+    constexpr std::integral_constant<int, 1> set1{};
+    auto load_stage = [&](const int (&rows)[2], auto set_tag) __attribute__((always_inline)) {
+        constexpr int S = decltype(set_tag)::value;
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            kreg[u] = make_uint4(0, 0, 0, 0);
-            vreg[u] = make_uint4(0, 0, 0, 0);
-            if (rows[u] >= 0) {
-                const size_t off = static_cast<size_t>(rows[u]) * kD + st_chunk * 8;
-                kreg[u] = *reinterpret_cast<const uint4*>(kbase + off);
-                vreg[u] = *reinterpret_cast<const uint4*>(vbase + off);
-            }
+            const size_t off = static_cast<size_t>(rows[u]) * kD + st_chunk * 8;
+            kreg[S][u] = *reinterpret_cast<const u32x4*>(kbase + off);
+            vreg[S][u] = *reinterpret_cast<const u32x4*>(vbase + off);
         }
     };
     // buf: which of the three stage buffers (0..2)
-    auto store_stage = [&](int buf) __attribute__((always_inline)) {
+    auto store_stage = [&](int buf, auto set_tag) __attribute__((always_inline)) {
+        constexpr int S = decltype(set_tag)::value;
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             unsigned char* kb = kvbuf + (2 * buf + u) * kSlotBytes;
-            *reinterpret_cast<uint4*>(kb + st_row * kKRow + st_chunk * 16) = kreg[u];
-            *reinterpret_cast<uint4*>(kb + kKTile + st_row * kVRow + st_chunk * 16) = vreg[u];
+            *reinterpret_cast<u32x4*>(kb + st_row * kKRow + st_chunk * 16) = kreg[S][u];
+            *reinterpret_cast<u32x4*>(kb + kKTile + st_row * kVRow + st_chunk * 16) = vreg[S][u];
         }
     };
 
@@ -374,7 +388,7 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
                 if (c4.w > row) acc[4 * a + 3] = NEG_INF;
             }
         } else {
-            mask_elements<0>(acc, ti.w, ti.cz, ti.vw, NEG_INF);
+            mask_elements<0>(acc, lane_keep_bits(ti.w, ti.cz, ti.vw, qi + 4 - 4 * hh, 4 - 4 * hh), __float_as_uint(NEG_INF));
         }
     };
 
@@ -392,10 +406,12 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 const int t = 2 * st + u;
-                int row = -1;
+                // rows past the sequence and tiles past the list read row 0 instead: their scores are masked, so the
+                // loads need no predicate (a predicated load makes the count of loads in flight path-dependent)
+                int row = 0;
                 if (t < ntiles) {
                     row = GATHER ? list[32 * t + st_row] : 32 * (DENSE ? t : list[t]) + st_row;
-                    if (row >= n) row = -1;
+                    if (row >= n) row = 0;
                 }
                 rows[u] = row;
             }
@@ -413,9 +429,13 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
         for (int st = 0; st < 2; ++st) {
             if (st < nstages) {
                 stage_rows(st, rows);
-                load_stage(rows);
-                store_stage(st);
+                load_stage(rows, set0);
+                store_stage(st, set0);
             }
+        }
+        if (kDeep) {
+            stage_rows(2, rows);
+            load_stage(rows, set0);                          // stage 2 waits in set 0, step 0 writes it
         }
         __syncthreads();
         bf16x8 k0[8], k1[8], vf[8], p0[2], p1[2];
@@ -428,17 +448,16 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
                 for (int db = 0; db < 4; ++db) oacc[db] = mfma32(vf[2 * db + t], pk[t], oacc[db]);
         };
         int buf = 0;                                         // buffer of stage st; st+1 is in buf+1, st+2 goes to buf+2 (mod 3)
-        for (int st = 0; st < nstages; ++st) {
+        // one step; (sk, sv): register set holding stage st+2 (written at the end), (lk, lv): set that receives stage st+3
+        auto step = [&](int st, auto store_tag, auto load_tag) __attribute__((always_inline)) {
             if (st > 0) __syncthreads();
             const int buf1 = buf == 2 ? 0 : buf + 1, buf2 = buf1 == 2 ? 0 : buf1 + 1;
             // list / bitmap words of the next stage are requested before the staging loads: the memory counters retire
             // in order, so waiting for them does not wait for the (younger) staging loads
             const TileInfo na = info(2 * st + 2), nb = info(2 * st + 3);
             const bool more = st + 2 < nstages;
-            if (more) {
-                stage_rows(st + 2, rows);
-                load_stage(rows);
-            }
+            stage_rows(st + (kDeep ? 3 : 2), rows);
+            load_stage(rows, load_tag);
             f32x16 s0, s1;
 #pragma unroll
             for (int e = 0; e < 16; ++e) s0[e] = s1[e] = 0.f;
@@ -504,10 +523,19 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
                     pv(p1);
                 }
             }
-            if (more) store_stage(buf2);
+            if (more) store_stage(buf2, store_tag);
             a = na;
             b = nb;
             buf = buf1;
+        };
+        for (int st = 0; st < nstages; st += 2) {
+            if (kDeep) {
+                step(st, set0, set1);
+                if (st + 1 < nstages) step(st + 1, set1, set0);
+            } else {
+                step(st, set0, set0);
+                if (st + 1 < nstages) step(st + 1, set0, set0);
+            }
         }
         __syncthreads();                                     // the ring and the list are reused by the next phase
     };
