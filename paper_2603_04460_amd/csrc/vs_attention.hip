@@ -61,15 +61,18 @@ constexpr int kKTile = 32 * kKRow;             // one 32-key tile of K
 constexpr int kVTile = 32 * kVRow;             // one 32-key tile of V
 constexpr int kSlotBytes = kKTile + kVTile;    // one LDS slot: a K tile, then the V tile of the same keys
 constexpr int kSlots = 6;                      // ring of three stages of two tiles
-constexpr int kListCap = 2048;                 // entries of the per-round gather list; block list: kListCap / nsub entries
+constexpr int kListCap = 2048;                 // block list: kListCap / nsub entries per round
+constexpr int kGatherCap = 4096;               // entries of the per-round gather list
 constexpr int kTbitWords = 1024;               // touched-block bits for up to 32768 key blocks (n <= 2^20)
-// ring | list (block numbers or gathered columns) | column word per listed block | offset windows per (sub-block, listed block) | touched bits | scratch
+// ring | block list | column word per listed block | offset windows per (sub-block, listed block) | touched bits | scratch | gather list
 constexpr size_t kListOff = kSlots * kSlotBytes;
 constexpr size_t kListVwOff = kListOff + kListCap * 4;
 constexpr size_t kListWOff = kListVwOff + (kListCap / 2) * 4;
 constexpr size_t kTbitOff = kListWOff + kListCap * 8;
 constexpr size_t kScratchOff = kTbitOff + kTbitWords * 4;
-constexpr size_t kSmemBytes = kScratchOff + 128;
+constexpr size_t kGatherOff = kScratchOff + 128;
+constexpr size_t kSmemBytes = kGatherOff + kGatherCap * 4;
+static_assert(kSmemBytes <= 160 * 1024, "LDS of one compute unit");
 constexpr uint64_t kAll63 = 0x7fffffffffffffffull;
 constexpr float kRescaleThreshold = 8.0f;      // log2 units: stale maxima up to 2^8 are tolerated
 
@@ -148,27 +151,6 @@ __device__ __forceinline__ void mask_elements(f32x16& acc, uint32_t keep, uint32
     if constexpr (A + 1 < 4) mask_elements<A + 1>(acc, keep, dead_bits);
 }
 
-// Ordered append of the flagged threads' values to list[base...]; returns the new length.  `parity` alternates
-// between calls so that one barrier per call is enough (the wave totals of call c+1 go to the other buffer while
-// slow wavefronts may still read those of call c).  The caller puts a barrier after its last call.
-__device__ __forceinline__ int wg_append(bool flag, int value, int* list, int base, int* wtot, int parity) {
-    const uint64_t bal = __ballot(flag);
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int pre = __popcll(bal & ((1ull << lane) - 1ull));
-    int* tot_buf = wtot + parity * kWaves;
-    if (lane == 0) tot_buf[w] = __popcll(bal);
-    __syncthreads();
-    int off = base, tot = 0;
-#pragma unroll
-    for (int i = 0; i < kWaves; ++i) {
-        const int c = tot_buf[i];
-        if (i < w) off += c;
-        tot += c;
-    }
-    if (flag) list[off + pre] = value;
-    return base + tot;
-}
-
 template <bool DENSE>
 __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams p) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -178,6 +160,7 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     uint64_t* const list_w = reinterpret_cast<uint64_t*>(smem + kListWOff);
     uint32_t* const tbits = reinterpret_cast<uint32_t*>(smem + kTbitOff);
     int* const wtot = reinterpret_cast<int*>(smem + kScratchOff);
+    int* const glist = reinterpret_cast<int*>(smem + kGatherOff);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -393,7 +376,7 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     };
 
     // ---- pipeline over the tiles of one phase ----
-    // GATHER == false: tile t is key block (DENSE ? t : list[t]);  GATHER == true: tile t is list[32 t .. 32 t + 31].
+    // GATHER == false: tile t is key block (DENSE ? t : list[t]);  GATHER == true: tile t is glist[32 t .. 32 t + 31].
     // A stage is two tiles (64 keys).  Three stages live in LDS: step s computes on stage s, prefetches K fragments of
     // stage s+1 (complete since the last barrier) and refills the buffer of stage s-1 with stage s+2, whose global loads
     // were started at the top of the step.  One barrier per step.  The two tiles of a stage go through one softmax
@@ -410,7 +393,7 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
                 // loads need no predicate (a predicated load makes the count of loads in flight path-dependent)
                 int row = 0;
                 if (t < ntiles) {
-                    row = GATHER ? list[32 * t + st_row] : 32 * (DENSE ? t : list[t]) + st_row;
+                    row = GATHER ? glist[32 * t + st_row] : 32 * (DENSE ? t : list[t]) + st_row;
                     if (row >= n) row = 0;
                 }
                 rows[u] = row;
@@ -418,7 +401,7 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
         };
         auto info = [&](int t) __attribute__((always_inline)) -> TileInfo {
             if (t >= ntiles) return TileInfo{false, false, 0ull, 0ull, 0u, nullptr};
-            if (GATHER) return gather_info(list + 32 * t);
+            if (GATHER) return gather_info(glist + 32 * t);
             return block_info(t);
         };
         // Every vector memory load issued so far (the Q fragments) is waited for here, once.  Left pending, the first
@@ -550,6 +533,64 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
         //    bit-reversed 32-bit window of T32 that ends at qb0 + r - 32 W (bits below 0 do not exist).
         const int qb0 = i0 >> 5;
         const int nwords = (nblk + 31) >> 5;
+        // Gather candidates: the listed columns <= i_last, whose number was prepared per 32-row block
+        // (column_count_kernel).  Thread t takes four consecutive entries per batch.  The first batch is requested
+        // here, unpredicated (entries past the count are dropped later), so that it travels together with the bitmap
+        // reads below instead of costing a round trip of its own after the slash part.
+        const int32_t* __restrict__ iv = p.idx_v + static_cast<size_t>(ih) * p.cap_v;
+        const int ncand = p.ncol32[static_cast<size_t>(ih) * p.nq32 + (i_last >> 5)];
+        int cand[4];
+        auto load_candidates = [&](int cursor) __attribute__((always_inline)) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) cand[u] = iv[min(cursor + 4 * tid + u, p.cap_v - 1)];
+        };
+        load_candidates(0);
+        bool cand_loaded = true;
+        int cursor = 0;
+        // One round of the gather list: batches of 4 * kThreads candidates are filtered (causal for the tile, not inside
+        // a marked block) and appended in order with ONE barrier per batch: position = kept entries of earlier
+        // wavefronts + of earlier lanes (four ballots) + of the lane's own earlier entries.  Wave totals alternate
+        // between two buffers so that a fast wavefront's next batch cannot overwrite totals still being read.
+        auto gather_round = [&]() -> int {
+            int count = 0, par = 0;
+            while (cursor < ncand && count + 4 * kThreads <= kGatherCap) {
+                if (!cand_loaded) load_candidates(cursor);
+                cand_loaded = false;
+                bool flag[4];
+                int pre = 0, tot = 0;
+                const uint64_t lt = (1ull << lane) - 1ull;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int c = cand[u];
+                    flag[u] = cursor + 4 * tid + u < ncand && c >= 0 && c <= i_last &&
+                              !((tbits[c >> 10] >> ((c >> 5) & 31)) & 1u);
+                    const uint64_t bal = __ballot(flag[u]);
+                    pre += __popcll(bal & lt);
+                    tot += __popcll(bal);
+                }
+                int* tot_buf = wtot + (1 + par) * kWaves;
+                if (lane == 0) tot_buf[wave] = tot;
+                __syncthreads();
+                int off = count + pre, all = 0;
+#pragma unroll
+                for (int i = 0; i < kWaves; ++i) {
+                    const int c = tot_buf[i];
+                    if (i < wave) off += c;
+                    all += c;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (flag[u]) glist[off++] = cand[u];
+                count += all;
+                par ^= 1;
+                cursor += 4 * kThreads;
+            }
+            __syncthreads();
+            const int padded = (count + 63) & ~63;
+            for (int t = count + tid; t < padded; t += kThreads) glist[t] = INT_MAX;
+            __syncthreads();
+            return count;
+        };
         for (int W = tid; W < nwords; W += kThreads) {
             uint32_t acc = 0;
             for (int r = 0; r < nsub; ++r) {
@@ -599,6 +640,9 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
             my_pos = before + incl - mine;
             nmarked = total;
         }
+        // The first round of the gather list is built together with the first round of the block list, so that the
+        // bitmap reads of the one and the ballots of the other share their waits.
+        int gcount = -1;
         for (int rbase = 0; rbase < nmarked; rbase += bcap) {
             const int count = min(bcap, nmarked - rbase);
             int pos = my_pos - rbase;
@@ -621,36 +665,16 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
                     list_w[r * bcap + e] = dlt < -31 ? 0ull : (window64(sbit, dlt + 33) & kAll63);
                 }
             }
-            __syncthreads();
+            if (gcount < 0) gcount = gather_round();         // ends with a barrier
+            else __syncthreads();
             run_phase(count, std::false_type{});
         }
         // 3. vertical part: causal columns outside the marked blocks, gathered row by row
-        const int32_t* __restrict__ iv = p.idx_v + static_cast<size_t>(ih) * p.cap_v;
-        // number of listed columns <= i_last: prepared per 32-row block (block_count_kernel)
-        const int ncand = p.ncol32[static_cast<size_t>(ih) * p.nq32 + (i_last >> 5)];
-        int cursor = 0;
-        while (cursor < ncand) {
-            int count = 0, par = 0;
-            while (cursor < ncand && count + 4 * kThreads <= kListCap) {
-                int col[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {                // one round trip to memory for four appends
-                    const int t = cursor + u * kThreads + tid;
-                    col[u] = t < ncand ? iv[t] : -1;
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const bool flag = col[u] >= 0 && col[u] <= i_last && !((tbits[col[u] >> 10] >> ((col[u] >> 5) & 31)) & 1u);
-                    count = wg_append(flag, col[u], list, count, wtot, par);
-                    par ^= 1;
-                }
-                cursor += 4 * kThreads;
-            }
-            __syncthreads();
-            const int padded = (count + 63) & ~63;
-            for (int t = count + tid; t < padded; t += kThreads) list[t] = INT_MAX;
-            __syncthreads();
-            run_phase((count + 31) >> 5, std::true_type{});
+        if (gcount < 0) gcount = gather_round();
+        while (true) {
+            run_phase((gcount + 31) >> 5, std::true_type{});
+            if (cursor >= ncand) break;
+            gcount = gather_round();
         }
     }
 
