@@ -119,6 +119,33 @@ def test_sparse_many_tiles_sampled_rows():
     check_attention(o, lse, ref_o, ref_lse, rows=rows)
 
 
+def test_sparse_several_gather_rounds():
+    """Two slash offsets and 9000 selected columns at n = 16384: late query tiles gather almost all of them, more than
+    one gather list holds (4096 entries), so the kernel runs several gather rounds per tile."""
+    n, hq, hk = 16384, 4, 1
+    rng = np.random.default_rng(17)
+    (q, k, v), (qb, kb, vb) = make_qkv(57, hq, hk, n)
+    iv, cv = lists([rng.choice(n, size=9000, replace=False)])
+    is_, cs = lists([[0, 1]])
+    o, lse, tiles = run_sparse(q, k, v, iv, cv, is_, cs)
+    rows = synth.sample_rows(17, n, 40, 72, 48)
+    ref_o, ref_lse = oracle.sparse_attention(qb, kb, vb, iv, cv, is_, cs, rows=rows)
+    check_attention(o, lse, ref_o, ref_lse, rows=rows)
+
+
+def test_sparse_several_block_rounds():
+    """Every 16th offset selected at n = 36000: every 32-key block is crossed by a selected diagonal, so late query
+    tiles list more blocks (1125) than one block list holds (1024 for a 64-row tile of four heads)."""
+    n, hq, hk = 36000, 4, 1
+    (q, k, v), (qb, kb, vb) = make_qkv(58, hq, hk, n)
+    iv, cv = lists([[0, 5, 17000]])
+    is_, cs = lists([list(range(0, n, 16))])
+    o, lse, tiles = run_sparse(q, k, v, iv, cv, is_, cs)
+    rows = synth.sample_rows(18, n, 32, 96, 32)
+    ref_o, ref_lse = oracle.sparse_attention(qb, kb, vb, iv, cv, is_, cs, rows=rows)
+    check_attention(o, lse, ref_o, ref_lse, rows=rows)
+
+
 def test_dense_sampled_rows_8192():
     n, hq, hk = 8192, 8, 2
     (q, k, v), (qb, kb, vb) = make_qkv(66, hq, hk, n)
