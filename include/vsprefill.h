@@ -4,7 +4,8 @@
  * The library implements the inference hot path of VSPrefill: VSIndexer scoring, the
  * cumulative-threshold budget with TopK, and causal vertical-slash sparse attention with the
  * per-query-tile index merge done inside the attention kernel, plus a dense causal attention
- * kernel on the same layout.
+ * kernel on the same layout and the vertical-slash aggregation of the dense attention map (the
+ * indexer's distillation target and the Attention Recall metric).
  *
  * Conventions shared by every call
  *   - Every tensor pointer is a DEVICE pointer owned by the caller, contiguous, 16-byte
@@ -162,6 +163,30 @@ int vs_sparse_prefill_tiled(const void* q, const void* k, const void* v, int q_h
  */
 int vs_dense_prefill(const void* q, const void* k, const void* v, int q_heads, int kv_heads, int64_t n,
                      float scale, void* o_bf16, float* lse, void* stream);
+
+size_t vs_aggregate_workspace(int q_heads, int kv_heads, int index_heads, int64_t n);
+
+/*
+ * Vertical-slash aggregation of the dense causal attention map (Sec. "Vertical-Slash Aggregation for Distillation
+ * Training", paragraph "Obtaining Ground Truth": A = softmax(Q K^T / sqrt(d)) summed along columns and along diagonals,
+ * both divided by n) and, optionally, the Attention Recall of a vertical-slash mask (Sec. "Sparse Attention
+ * Formulation", Eq. R(S)).  A is never stored: it is recomputed tile by tile from Q, K and the row normalisers.
+ *   q           [q_heads, n, 128] bf16;  k  [kv_heads, n, 128] bf16 (both already carry RoPE)
+ *   lse         [q_heads, n] fp32 natural-log row normalisers as written by vs_dense_prefill for the same q, k and
+ *               scale, or NULL: then a first sweep over the scores computes them into the workspace
+ *   out_heads   q_heads: one pair of vectors per query head;  kv_heads: the mean over the query heads of each KV group
+ *   a_v, a_s    [out_heads, n] fp32 out.  a_v[., j] = (1/n) sum_i A[i, j];  a_s[., o] = (1/n) sum_i A[i, i - o].
+ *               Each row sums to 1.  Accumulated with float atomics: the last bits depend on the order of execution.
+ *   recall      [out_heads] fp32 out or NULL.  When given, idx_v / cnt_v / cap_v / idx_s / cnt_s / cap_s / index_heads
+ *               describe the mask as for vs_sparse_prefill (element-exact rule) and
+ *               recall[.] = (1/n) sum over kept (i, j), j <= i, of A[i, j].  When NULL the list arguments are ignored.
+ * Arithmetic: bf16 MFMA for Q K^T with fp32 accumulation, fp32 exponentials and sums.
+ * Workspace from vs_aggregate_workspace (index_heads = 0 when no recall is wanted); errors as for the other calls.
+ */
+int vs_aggregate(const void* q, const void* k, int q_heads, int kv_heads, int64_t n, float scale, const float* lse,
+                 int out_heads, float* a_v, float* a_s, const int32_t* idx_v, const int32_t* cnt_v, int cap_v,
+                 const int32_t* idx_s, const int32_t* cnt_s, int cap_s, int index_heads, float* recall, void* ws,
+                 size_t ws_bytes, void* stream);
 
 /*
  * Number of MFMA tiles the last vs_sparse_prefill that used this workspace executed.  One tile is

@@ -13,7 +13,7 @@ _lib = None
 EXPORTS = [
     "vs_rope_apply", "vs_index_score_workspace", "vs_index_score", "vs_select_budget_workspace", "vs_select_budget",
     "vs_sparse_prefill_workspace", "vs_sparse_prefill", "vs_sparse_prefill_tiled", "vs_dense_prefill",
-    "vs_sparse_prefill_tiles",
+    "vs_sparse_prefill_tiles", "vs_aggregate_workspace", "vs_aggregate",
     "vs_strerror", "vs_last_hip_error", "vs_version",
 ]
 
@@ -65,6 +65,9 @@ def _load():
     L.vs_sparse_prefill_tiled.argtypes = [vp, vp, vp, i32, i32, i64, f32, vp, vp, i32, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
     L.vs_dense_prefill.argtypes = [vp, vp, vp, i32, i32, i64, f32, vp, vp, vp]
     L.vs_sparse_prefill_tiles.argtypes = [vp, sz, vp, ctypes.POINTER(ctypes.c_int64)]
+    L.vs_aggregate_workspace.argtypes = [i32, i32, i32, i64]
+    L.vs_aggregate_workspace.restype = sz
+    L.vs_aggregate.argtypes = [vp, vp, i32, i32, i64, f32, vp, i32, vp, vp, vp, vp, i32, vp, vp, i32, i32, vp, vp, sz, vp]
     L.vs_strerror.argtypes = [i32]
     L.vs_strerror.restype = ctypes.c_char_p
     L.vs_last_hip_error.restype = i32
@@ -216,6 +219,41 @@ def sparse_prefill_tiles(ws, stream=None):
     _check(_load().vs_sparse_prefill_tiles(_ptr(ws), ws.numel() * ws.element_size(), _stream(stream), ctypes.byref(out)),
            "vs_sparse_prefill_tiles")
     return out.value
+
+
+def aggregate_workspace(q_heads, kv_heads, index_heads, n):
+    return _load().vs_aggregate_workspace(q_heads, kv_heads, index_heads, n)
+
+
+def aggregate(q, k, a_v, a_s, ws, lse=None, lists=None, recall=None, scale=None, stream=None):
+    """a_v, a_s: [out_heads, n] fp32 with out_heads = q_heads or kv_heads.  lists = (idx_v, cnt_v, idx_s, cnt_s) and
+    recall [out_heads] fp32 go together."""
+    import torch
+    _dev(q, torch.bfloat16, "q"); _dev(k, torch.bfloat16, "k"); _dev(a_v, torch.float32, "a_v"); _dev(a_s, torch.float32, "a_s")
+    q_heads, n, d = q.shape
+    kv_heads = k.shape[0]
+    out_heads = a_v.shape[0]
+    assert d == 128 and k.shape == (kv_heads, n, 128) and a_v.shape == (out_heads, n) and a_s.shape == a_v.shape
+    if lse is not None:
+        _dev(lse, torch.float32, "lse")
+        assert lse.shape == (q_heads, n)
+    idx_v = cnt_v = idx_s = cnt_s = None
+    cap_v = cap_s = index_heads = 0
+    if recall is not None:
+        _dev(recall, torch.float32, "recall")
+        assert recall.numel() == out_heads and lists is not None
+        idx_v, cnt_v, idx_s, cnt_s = lists
+        _dev(idx_v, torch.int32, "idx_v"); _dev(idx_s, torch.int32, "idx_s")
+        _dev(cnt_v, torch.int32, "cnt_v"); _dev(cnt_s, torch.int32, "cnt_s")
+        index_heads = idx_v.shape[0]
+        assert idx_s.shape[0] == index_heads and cnt_v.numel() == index_heads and cnt_s.numel() == index_heads
+        cap_v, cap_s = idx_v.shape[1], idx_s.shape[1]
+    scale = 128 ** -0.5 if scale is None else scale
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    _check(_load().vs_aggregate(_ptr(q), _ptr(k), q_heads, kv_heads, n, scale, _ptr(lse), out_heads, _ptr(a_v), _ptr(a_s),
+                                _ptr(idx_v), _ptr(cnt_v), cap_v, _ptr(idx_s), _ptr(cnt_s), cap_s, index_heads,
+                                _ptr(recall), _ptr(ws), ws_bytes, _stream(stream)), "vs_aggregate")
+    return a_v, a_s
 
 
 def dense_prefill(q, k, v, o, lse=None, scale=None, stream=None):

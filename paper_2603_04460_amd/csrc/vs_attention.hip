@@ -42,6 +42,7 @@
 #include <type_traits>
 
 #include "vs_common.h"
+#include "vs_device.h"
 
 namespace {
 
@@ -96,14 +97,6 @@ struct AttnParams {
     int nq32;                       // entries per head of ncol32
     unsigned long long* tile_counter;
 };
-
-__device__ __forceinline__ uint64_t window64(const uint32_t* __restrict__ bm, int bitpos) {
-    const int w = bitpos >> 5, sh = bitpos & 31;
-    const uint32_t a = bm[w], b = bm[w + 1], c = bm[w + 2];
-    uint64_t r = ((static_cast<uint64_t>(b) << 32) | a) >> sh;
-    if (sh) r |= static_cast<uint64_t>(c) << (64 - sh);
-    return r;
-}
 
 __device__ __forceinline__ float half_swap_max(float x) {
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
@@ -703,23 +696,6 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
         }
     }
     if (p.tile_counter && lane == 0 && tiles_done) atomicAdd(p.tile_counter, static_cast<unsigned long long>(tiles_done));
-}
-
-// ---- index lists -> bitmaps ----
-__global__ void fill_zero_kernel(uint32_t* p, size_t words) {
-    const size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (i < words) p[i] = 0u;
-}
-
-__global__ void set_bits_kernel(const int32_t* idx, const int32_t* cnt, int cap, int n, uint32_t* bits, int words_per_head,
-                                int bit_shift) {
-    const int ih = blockIdx.y;
-    const int t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= min(cnt[ih], cap)) return;
-    const int e = idx[static_cast<size_t>(ih) * cap + t];
-    if (e < 0 || e >= n) return;
-    const int bit = e + bit_shift;
-    atomicOr(bits + static_cast<size_t>(ih) * words_per_head + (bit >> 5), 1u << (bit & 31));
 }
 
 // t32 bit t = any selected offset in [32 t - 31, 32 t + 31]
