@@ -29,11 +29,10 @@
 //      an element then costs a bit-field extract and a bitwise select.  Interior tiles whose window
 //      is all ones skip the mask, row blocks whose window is empty skip the tile.
 //
-// Staging: global loads of a stage go to registers and from there to LDS.  The sparse kernel keeps two
-// register sets and issues the loads of stage s+3 while stage s is computed (they are written to LDS one
-// step later), so a load has a full step to arrive; the dense kernel, which has no registers to spare,
-// loads one step ahead.  Loads are never predicated: a predicated load would make the number of loads in
-// flight path-dependent and force a full wait before every LDS write.
+// Staging: K / V rows go from global memory straight into LDS (global_load_lds_dwordx4: no staging registers, no LDS
+// store instructions).  The loads of stage s+2 are issued at the top of step s into the buffer that stage s-1 has just
+// left; each wavefront waits for its own loads (vmcnt) before the barrier that opens step s+1, which publishes them.
+// Loads are never predicated: rows that do not exist read row 0, whose scores are masked.
 #include <hip/hip_runtime.h>
 #include <limits.h>
 #include <math.h>
@@ -56,11 +55,14 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kD = 128;
 constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / 64;
-constexpr int kKRow = 272;                     // K row: 256 B + 16 B pad, conflict-free for the 16-byte fragment reads
-constexpr int kVRow = 320;                     // V row: 256 B + 64 B pad: the 4 rows x 64 B of a transposing read tile all 64 banks
-constexpr int kKTile = 32 * kKRow;             // one 32-key tile of K
-constexpr int kVTile = 32 * kVRow;             // one 32-key tile of V
-constexpr int kSlotBytes = kKTile + kVTile;    // one LDS slot: a K tile, then the V tile of the same keys
+// A tile is staged with loads that write LDS directly: one wavefront instruction deposits its 64 16-byte pieces
+// back to back, which makes 4 rows of 256 B a contiguous 1 KB group.  Groups are 64 B apart and the pieces are rotated
+// inside a group so that fragment reads spread over all banks:
+//   K (16-byte reads, 16 rows at one chunk c): chunk c of row r sits at 64 (c / 4) + 16 ((c + r) % 4) of its row
+//   V (transposing reads, 4 rows x 64 B):      byte x of row r sits at 64 ((x / 64 + r) % 4) + x % 64 of its row
+constexpr int kGroupBytes = 4 * 256 + 64;      // four rows and the gap to the next group
+constexpr int kTileBytes = 8 * kGroupBytes;    // one 32-key tile of K or V
+constexpr int kSlotBytes = 2 * kTileBytes;     // one LDS slot: a K tile, then the V tile of the same keys
 constexpr int kSlots = 6;                      // ring of three stages of two tiles
 constexpr int kListCap = 2048;                 // block list: kListCap / nsub entries per round
 constexpr int kGatherCap = 4096;               // entries of the per-round gather list
@@ -144,6 +146,16 @@ __device__ __forceinline__ void mask_elements(f32x16& acc, uint32_t keep, uint32
     if constexpr (A + 1 < 4) mask_elements<A + 1>(acc, keep, dead_bits);
 }
 
+// 16 bytes per lane from global memory straight into LDS: lane L's piece lands at lds_base + 16 L (lds_base is
+// wave-uniform).  Written as an instruction rather than through the builtin: the compiler orders every later LDS read
+// behind a builtin load it cannot tell apart (a full vmcnt wait in the middle of the pipeline); here the kernel itself
+// waits (vmcnt) before the barrier that publishes a stage.
+__device__ __forceinline__ void lds_load16(const void* gsrc, const void* lds_base) {
+    const uint32_t base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+        (const __attribute__((address_space(3))) void*)lds_base));
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(base), "v"(gsrc) : "memory", "m0");
+}
+
 template <bool DENSE>
 __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams p) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -212,53 +224,52 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
 
     // ---- staging: a stage is two 32-key tiles; thread moves 16-byte chunk (tid & 15) of row (tid >> 4) of K and V of each ----
     const int st_row = tid >> 4, st_chunk = tid & 15;
-    // two register sets: the global loads of stage st+3 are issued at the top of step st and written to LDS at the end
-    // of step st+1, so a load has two steps to arrive
-    u32x4 kreg[2][2], vreg[2][2];
-    // the dense kernel has no registers to spare for a second set: it loads one step ahead
-    constexpr bool kDeep = !DENSE;
-    constexpr std::integral_constant<int, 0> set0{};
-    constexpr std::integral_constant<int, 1> set1{};
-    auto load_stage = [&](const int (&rows)[2], auto set_tag) __attribute__((always_inline)) {
-        constexpr int S = decltype(set_tag)::value;
+    // thread (wavefront w, lane L) fills piece L of group w of a tile: row 4w + L/16 (= st_row); which 16-byte chunk of the
+    // row that piece holds follows from the rotations above
+    typedef const __attribute__((address_space(1))) void* gptr_t;
+    typedef __attribute__((address_space(3))) void* lptr_t;
+    const int st_rho = (lane >> 4) & 3;
+    const int st_ck = 4 * ((lane >> 2) & 3) + (((lane & 3) - st_rho) & 3);          // K chunk of this piece
+    const int st_cv = 4 * ((((lane >> 2) & 3) - st_rho) & 3) + (lane & 3);          // V chunk of this piece
+    // buf: which of the three stage buffers (0..2).  The loads complete in the background (vmcnt).
+    auto load_stage = [&](const int (&rows)[2], int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            const size_t off = static_cast<size_t>(rows[u]) * kD + st_chunk * 8;
-            kreg[S][u] = *reinterpret_cast<const u32x4*>(kbase + off);
-            vreg[S][u] = *reinterpret_cast<const u32x4*>(vbase + off);
-        }
-    };
-    // buf: which of the three stage buffers (0..2)
-    auto store_stage = [&](int buf, auto set_tag) __attribute__((always_inline)) {
-        constexpr int S = decltype(set_tag)::value;
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            unsigned char* kb = kvbuf + (2 * buf + u) * kSlotBytes;
-            *reinterpret_cast<u32x4*>(kb + st_row * kKRow + st_chunk * 16) = kreg[S][u];
-            *reinterpret_cast<u32x4*>(kb + kKTile + st_row * kVRow + st_chunk * 16) = vreg[S][u];
+            unsigned char* dst = kvbuf + (2 * buf + u) * kSlotBytes + wave * kGroupBytes;
+            const size_t off = static_cast<size_t>(rows[u]) * kD;
+            lds_load16(kbase + off + st_ck * 8, dst);
+            lds_load16(vbase + off + st_cv * 8, dst + kTileBytes);
         }
     };
 
     // ---- pieces of one (row block, 32-key tile) unit ----
     const int li = lane & 15, dsel = (lane >> 4) & 1;
-    const int k_off = qi * kKRow + hh * 16;
-    const int v_off = kKTile + (4 * hh + (li >> 2)) * kVRow + (16 * dsel + 4 * (li & 3)) * 2;
+    // K fragment kk: chunk 2 kk + hh of row qi -> 64 (kk / 2) + 16 ((2 kk + hh + qi) % 4): two per-lane bases (kk even / odd)
+    const int k_row = (qi >> 2) * kGroupBytes + (qi & 3) * 256;
+    const int k_off0 = k_row + 16 * ((hh + qi) & 3), k_off2 = k_row + 16 * ((hh + qi + 2) & 3);
+    // V fragment j: rows 4 hh + li / 4 + 16 (j % 2) (+ 8), bytes 64 (j / 2) + 32 dsel + 8 (li % 4) .. + 7
+    const int v_rho = (li >> 2) & 3;
+    const int v_lane = kTileBytes + hh * kGroupBytes + v_rho * 256 + 32 * dsel + 8 * (li & 3);
+    int v_off[4];
+#pragma unroll
+    for (int sgr = 0; sgr < 4; ++sgr) v_off[sgr] = v_lane + 64 * ((sgr + v_rho) & 3);
     typedef __attribute__((address_space(3))) bf16x4t* lds_ptr_t;
     // slot: which of the six tile slots (wave-uniform)
     auto read_k = [&](int slot, bf16x8 (&kf)[8]) __attribute__((always_inline)) {
-        const unsigned char* kt = kvbuf + slot * kSlotBytes + k_off;
+        const unsigned char* kt = kvbuf + slot * kSlotBytes;
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) kf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(kt + kk * 32));
+        for (int kk = 0; kk < 8; ++kk)
+            kf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(kt + ((kk & 1) ? k_off2 : k_off0) + 64 * (kk >> 1)));
     };
     // transposing LDS read: within 16 lanes, lane i addresses row i/4, 4 columns at 4 (i%4); it receives column i of
     // those 4 rows, i.e. 4 consecutive keys of one d
     auto read_v = [&](int slot, bf16x8 (&vf)[8]) __attribute__((always_inline)) {
-        const unsigned char* va = kvbuf + slot * kSlotBytes + v_off;
+        const unsigned char* va = kvbuf + slot * kSlotBytes;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {                      // j = 2 db + t16: d block db, keys 16 t16 ..
-            const unsigned char* a0 = va + 16 * (j & 1) * kVRow + 64 * (j >> 1);
+            const unsigned char* a0 = va + v_off[j >> 1] + 4 * (j & 1) * kGroupBytes;
             const bf16x4t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr_t)(a0));
-            const bf16x4t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr_t)(a0 + 8 * kVRow));
+            const bf16x4t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr_t)(a0 + 2 * kGroupBytes));
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 vf[j][e] = lo[e];
@@ -383,7 +394,7 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
             for (int u = 0; u < 2; ++u) {
                 const int t = 2 * st + u;
                 // rows past the sequence and tiles past the list read row 0 instead: their scores are masked, so the
-                // loads need no predicate (a predicated load makes the count of loads in flight path-dependent)
+                // loads need no predicate
                 int row = 0;
                 if (t < ntiles) {
                     row = GATHER ? glist[32 * t + st_row] : 32 * (DENSE ? t : list[t]) + st_row;
@@ -405,14 +416,10 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
         for (int st = 0; st < 2; ++st) {
             if (st < nstages) {
                 stage_rows(st, rows);
-                load_stage(rows, set0);
-                store_stage(st, set0);
+                load_stage(rows, st);
             }
         }
-        if (kDeep) {
-            stage_rows(2, rows);
-            load_stage(rows, set0);                          // stage 2 waits in set 0, step 0 writes it
-        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);                  // the barrier publishes only what has arrived
         __syncthreads();
         bf16x8 k0[8], k1[8], vf[8], p0[2], p1[2];
         TileInfo a = info(0), b = info(1);
@@ -424,16 +431,21 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
                 for (int db = 0; db < 4; ++db) oacc[db] = mfma32(vf[2 * db + t], pk[t], oacc[db]);
         };
         int buf = 0;                                         // buffer of stage st; st+1 is in buf+1, st+2 goes to buf+2 (mod 3)
-        // one step; (sk, sv): register set holding stage st+2 (written at the end), (lk, lv): set that receives stage st+3
-        auto step = [&](int st, auto store_tag, auto load_tag) __attribute__((always_inline)) {
-            if (st > 0) __syncthreads();
+        // one step
+        auto step = [&](int st) __attribute__((always_inline)) {
+            if (st > 0) {
+                __builtin_amdgcn_s_waitcnt(0x0F70);          // this wavefront's part of stage st+1 has arrived
+                __syncthreads();
+            }
             const int buf1 = buf == 2 ? 0 : buf + 1, buf2 = buf1 == 2 ? 0 : buf1 + 1;
             // list / bitmap words of the next stage are requested before the staging loads: the memory counters retire
             // in order, so waiting for them does not wait for the (younger) staging loads
             const TileInfo na = info(2 * st + 2), nb = info(2 * st + 3);
             const bool more = st + 2 < nstages;
-            stage_rows(st + (kDeep ? 3 : 2), rows);
-            load_stage(rows, load_tag);
+            if (more) {                                      // into the buffer of stage st-1, free since the barrier
+                stage_rows(st + 2, rows);
+                load_stage(rows, buf2);
+            }
             f32x16 s0, s1;
 #pragma unroll
             for (int e = 0; e < 16; ++e) s0[e] = s1[e] = 0.f;
@@ -499,19 +511,13 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
                     pv(p1);
                 }
             }
-            if (more) store_stage(buf2, store_tag);
             a = na;
             b = nb;
             buf = buf1;
         };
         for (int st = 0; st < nstages; st += 2) {
-            if (kDeep) {
-                step(st, set0, set1);
-                if (st + 1 < nstages) step(st + 1, set1, set0);
-            } else {
-                step(st, set0, set0);
-                if (st + 1 < nstages) step(st + 1, set0, set0);
-            }
+            step(st);
+            if (st + 1 < nstages) step(st + 1);
         }
         __syncthreads();                                     // the ring and the list are reused by the next phase
     };
