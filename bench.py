@@ -29,9 +29,10 @@ from paper_2603_04460_amd import synth  # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0           # MI355X dense bf16 MFMA
 FLOP_PER_TILE = 4 * 128 * 32 * 32   # QK^T and PV of a 32-row x 32-key tile at head_dim 128
-# HBM bytes per launch of the sparse attention kernel at the default workload, from the rocprofv3 --pmc
-# FETCH_SIZE / WRITE_SIZE runs summarised under profiles/ (None until measured for this workload)
-MEASURED_TRAFFIC_BYTES = None
+# HBM bytes per launch of the sparse attention kernel at the default workload (C4, n = 131072, tau = 0.9), from the
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/c4_128k_hbm_counters.txt:
+# 8743081.5 KiB fetched x 0.99998 (plain-copy calibration) + 1052674.5 KiB written.  Other workloads report null.
+MEASURED_TRAFFIC_BYTES = 10030675086
 
 
 def log(*a):
@@ -303,7 +304,8 @@ def main():
                    "tile_efficiency": pairs / (tiles * 1024.0)},
         "paper_context": "paper reports 4.95x (8.42x aggressive) over FlashAttention at 128k on unstated NVIDIA hardware",
         "roofline": {"kernel": "vs_attention_kernel<sparse>", "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES if (args.config == 4 and n == 131072 and args.tau == 0.9) else None,
                      "flop_per_launch": exec_flop, "avg_launch_ms": t_att, "executed_tiles": tiles},
     }
     if not args.no_cpu_baseline:
