@@ -465,7 +465,8 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
                     for (int kk = 0; kk < 8; ++kk) s0 = mfma32(k0[kk], qf[kk], s0);
                 }
             } else {
-                // one chain after the other: the second tile's fragments can reuse the registers of the first
+                // one chain after the other; the second tile's fragments are requested before the first chain starts
+                if (b.live) read_k(2 * buf + 1, k1);
                 if (a.live) {
                     ++tiles_done;
 #pragma unroll
@@ -473,7 +474,6 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
                 }
                 if (b.live) {
                     ++tiles_done;
-                    read_k(2 * buf + 1, k1);
 #pragma unroll
                     for (int kk = 0; kk < 8; ++kk) s1 = mfma32(k1[kk], qf[kk], s1);
                 }
