@@ -71,6 +71,18 @@ def test_host_side_argument_checks():
     assert L.vs_index_score(vp(p), vp(p), 1, 64, ctypes.byref(w), vp(p), vp(p), vp(p), 1 << 20, None) == -1
     w = binding._Indexer(p, p, p, p, 0.0, 0.0, 256, 1)
     assert L.vs_index_score(vp(p), vp(p), 1, 64, ctypes.byref(w), vp(p), vp(p), vp(p), 16, None) == -3
+    # vs_aggregate(q, k, q_heads, kv_heads, n, scale, lse, out_heads, a_v, a_s, idx_v, cnt_v, cap_v, idx_s, cnt_s, cap_s,
+    #              index_heads, recall, ws, ws_bytes, stream)
+    agg = lambda *a: L.vs_aggregate(*a)
+    big = 1 << 20
+    assert agg(None, vp(p), 4, 1, 64, 0.1, None, 4, vp(p), vp(p), None, None, 0, None, None, 0, 0, None, vp(p), big, None) == -1
+    assert agg(vp(p), vp(p), 4, 3, 64, 0.1, None, 4, vp(p), vp(p), None, None, 0, None, None, 0, 0, None, vp(p), big, None) == -2
+    assert agg(vp(p), vp(p), 4, 1, 64, 0.1, None, 2, vp(p), vp(p), None, None, 0, None, None, 0, 0, None, vp(p), big, None) == -2
+    assert agg(vp(p), vp(p), 4, 1, 64, 0.1, None, 4, vp(p), vp(p), None, None, 0, None, None, 0, 0, None, vp(p), 64, None) == -3
+    # a recall needs the lists
+    assert agg(vp(p), vp(p), 4, 1, 64, 0.1, None, 4, vp(p), vp(p), None, None, 0, None, None, 0, 1, vp(p), vp(p), big, None) == -1
+    assert vs.aggregate_workspace(32, 8, 8, 131072) >= 32 * 131072 * 4
+    assert vs.aggregate_workspace(32, 8, 0, 131072) == 32 * 131072 * 4
 
 
 def test_product_path_does_not_import_the_oracle():
