@@ -71,6 +71,46 @@ def test_sparse_random_lists(hq, hk, n, nv, ns, per_q):
     assert tiles * 1024 >= live.sum()
 
 
+def test_sparse_randomized_sweep():
+    """36 seeded random cases in one process: lengths 1 .. 2600 (ragged against every tile size), head layouts with
+    group sizes 1, 2, 4 and 8, list sizes from empty to a third of the sequence, scattered and run-shaped offsets, with
+    and without the diagonal, exact and tile-granular mode, per-KV-head and per-query-head lists."""
+    rng = np.random.default_rng(20260304)
+    layouts = [(1, 1), (2, 1), (4, 1), (4, 2), (8, 2), (8, 1), (4, 4)]
+    for case in range(36):
+        hq, hk = layouts[int(rng.integers(len(layouts)))]
+        n = int(rng.choice([1, 2, 31, 32, 33, 63, 64, 65, 255, 256, 257, 500, 1000, 1023, 1025, 1777, 2600]))
+        per_q = bool(rng.integers(2)) and hq != hk
+        ih = hq if per_q else hk
+        nv = int(rng.integers(0, max(1, n // 3) + 1))
+        ns = int(rng.integers(0, max(1, n // 6) + 1))
+        runs = bool(rng.integers(2))
+        gran = 32 if rng.integers(3) == 0 else None
+        sv, ss = [], []
+        for _ in range(ih):
+            cols = set(rng.choice(n, size=min(nv, n), replace=False).tolist()) if nv else set()
+            offs = set() if rng.integers(4) == 0 else {0}
+            guard = 0
+            while len(offs) < min(ns, n) and guard < 10000:
+                start = int(rng.integers(0, n))
+                length = int(rng.integers(1, 40)) if runs else 1
+                offs.update(range(start, min(n, start + length)))
+                guard += 1
+            sv.append(cols)
+            ss.append(offs)
+        iv, cv = lists(sv)
+        is_, cs = lists(ss)
+        (q, k, v), (qb, kb, vb) = make_qkv(5000 + case, hq, hk, n)
+        o, lse, tiles = run_sparse(q, k, v, iv, cv, is_, cs, granularity=gran)
+        ref_o, ref_lse, live = oracle.sparse_attention(qb, kb, vb, iv, cv, is_, cs, return_live=True, granularity=gran or 1)
+        try:
+            check_attention(o, lse, ref_o, ref_lse)
+            assert tiles * 1024 >= live.sum()
+        except AssertionError as e:
+            raise AssertionError("case %d: heads %d/%d n %d nv %d ns %d runs %s per_q %s g %s: %s"
+                                 % (case, hq, hk, n, nv, ns, runs, per_q, gran, e))
+
+
 def test_sparse_edge_cases():
     n, hq, hk = 300, 4, 1
     (q, k, v), (qb, kb, vb) = make_qkv(7, hq, hk, n)
