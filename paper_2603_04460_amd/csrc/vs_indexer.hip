@@ -24,7 +24,7 @@ constexpr int kTokensPerWg = 256;          // 4 wavefronts x 2 blocks of 32 toke
 constexpr int kChunkU = 64;                // hidden units staged in LDS at a time
 constexpr int kWRowBytes = 512 + 32;       // 256 bf16 + pad (conflict-free 16-byte fragment reads)
 constexpr int kMaxDh = 1024;
-constexpr size_t kSmemBytes = 2 * kChunkU * kWRowBytes + 3 * kMaxDh * 4;
+constexpr size_t kSmemBytes = 2 * kChunkU * kWRowBytes + 3 * kMaxDh * 4 + 64;
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
     uint32_t u = __float_as_uint(f);
@@ -76,7 +76,8 @@ __global__ __launch_bounds__(kThreads) void indexer_logits_kernel(const uint16_t
                                                                   const uint16_t* __restrict__ w_lo, const float* __restrict__ b_U,
                                                                   const float* __restrict__ W_V, const float* __restrict__ W_S,
                                                                   float b_V, float b_S, float* __restrict__ logit_v,
-                                                                  float* __restrict__ logit_s) {
+                                                                  float* __restrict__ logit_s, float2* __restrict__ part,
+                                                                  int nblk) {
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char* const whi = smem;
     unsigned char* const wlo = smem + kChunkU * kWRowBytes;
@@ -87,13 +88,15 @@ __global__ __launch_bounds__(kThreads) void indexer_logits_kernel(const uint16_t
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, hh = lane >> 5;
     const int g = blockIdx.y;
-    const int tok0 = blockIdx.x * kTokensPerWg + 64 * wave;
+    float* const red = sWS + d_h;                          // 4 wavefronts x (max_v, sum_v, max_s, sum_s)
 
     for (int u = tid; u < d_h; u += kThreads) {
         sbU[u] = b_U[u];
         sWV[u] = W_V[u];
         sWS[u] = W_S[u];
     }
+    const int blk = blockIdx.x;
+    const int tok0 = blk * kTokensPerWg + 64 * wave;
 
     // X^T fragments: lane holds token col, features 16 kk + 8 hh .. + 7 (kk < 8: K, kk >= 8: V)
     bf16x8 xf[2][16];
@@ -156,52 +159,103 @@ __global__ __launch_bounds__(kThreads) void indexer_logits_kernel(const uint16_t
             }
         }
     }
+    // logits out; (max, sum of exp) of the block's tokens per direction for the softmax over all positions
+    float mv = -INFINITY, ms = -INFINITY, v2[2], s2[2];
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb) {
-        const float v = half_swap_sum(lv[tb]) + b_V, s = half_swap_sum(ls[tb]) + b_S;
+        v2[tb] = half_swap_sum(lv[tb]) + b_V;
+        s2[tb] = half_swap_sum(ls[tb]) + b_S;
         const int tok = tok0 + 32 * tb + col;
-        if (hh == 0 && tok < n) {
-            logit_v[static_cast<size_t>(g) * n + tok] = v;
-            logit_s[static_cast<size_t>(g) * n + tok] = s;
+        if (tok < n) {
+            if (hh == 0) {
+                logit_v[static_cast<size_t>(g) * n + tok] = v2[tb];
+                logit_s[static_cast<size_t>(g) * n + tok] = s2[tb];
+            }
+            mv = fmaxf(mv, v2[tb]);
+            ms = fmaxf(ms, s2[tb]);
         }
+    }
+#pragma unroll
+    for (int d = 16; d >= 1; d >>= 1) {                     // both halves hold the same 32 tokens
+        mv = fmaxf(mv, __shfl_xor(mv, d));
+        ms = fmaxf(ms, __shfl_xor(ms, d));
+    }
+    float ev = 0.f, es = 0.f;
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+        if (tok0 + 32 * tb + col < n) {
+            ev += expf(v2[tb] - mv);
+            es += expf(s2[tb] - ms);
+        }
+    }
+#pragma unroll
+    for (int d = 16; d >= 1; d >>= 1) {
+        ev += __shfl_xor(ev, d);
+        es += __shfl_xor(es, d);
+    }
+    if (lane == 0) {
+        red[4 * wave] = mv;
+        red[4 * wave + 1] = ev;
+        red[4 * wave + 2] = ms;
+        red[4 * wave + 3] = es;
+    }
+    __syncthreads();
+    if (tid < 2) {                                          // thread 0: vertical, thread 1: slash
+        float m = -INFINITY, e = 0.f;
+        for (int w = 0; w < 4; ++w) m = fmaxf(m, red[4 * w + 2 * tid]);
+        for (int w = 0; w < 4; ++w) {
+            const float mw = red[4 * w + 2 * tid];
+            if (mw > -INFINITY) e += red[4 * w + 2 * tid + 1] * expf(mw - m);
+        }
+        part[(static_cast<size_t>(g) * 2 + tid) * nblk + blk] = make_float2(m, e);
     }
 }
 
-// in-place softmax over the n positions of one (head, direction)
-__global__ __launch_bounds__(1024) void softmax_rows_kernel(float* a_v, float* a_s, int n) {
-    __shared__ float red[16];
-    float* x = (blockIdx.y == 0 ? a_v : a_s) + static_cast<size_t>(blockIdx.x) * n;
+// Second stage of the softmax over the n positions of one (head, direction): every workgroup folds the per-block
+// (max, sum) pairs into the global pair (a few hundred values, cheaper than another launch) and normalises its own
+// 1024 logits in place.
+__global__ __launch_bounds__(256) void softmax_finish_kernel(float* a_v, float* a_s, int n, const float2* __restrict__ part, int nblk) {
+    __shared__ float red[8];
+    const int g = blockIdx.y, dir = blockIdx.z;
+    const float2* pp = part + (static_cast<size_t>(g) * 2 + dir) * nblk;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     float m = -INFINITY;
-    for (int i = tid; i < n; i += 1024) m = fmaxf(m, x[i]);
+    for (int i = tid; i < nblk; i += 256) m = fmaxf(m, pp[i].x);
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d));
     if (lane == 0) red[wave] = m;
     __syncthreads();
-    m = red[0];
-    for (int w = 1; w < 16; ++w) m = fmaxf(m, red[w]);
-    __syncthreads();
-    float s = 0.f;
-    for (int i = tid; i < n; i += 1024) s += expf(x[i] - m);
+    m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float e = 0.f;
+    for (int i = tid; i < nblk; i += 256) {
+        const float2 q = pp[i];
+        if (q.x > -INFINITY) e += q.y * expf(q.x - m);
+    }
 #pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d);
-    if (lane == 0) red[wave] = s;
+    for (int d = 32; d >= 1; d >>= 1) e += __shfl_xor(e, d);
+    if (lane == 0) red[4 + wave] = e;
     __syncthreads();
-    s = 0.f;
-    for (int w = 0; w < 16; ++w) s += red[w];
-    const float inv = 1.f / s;
-    for (int i = tid; i < n; i += 1024) x[i] = expf(x[i] - m) * inv;
+    const float inv = 1.f / (red[4] + red[5] + red[6] + red[7]);
+    float* x = (dir == 0 ? a_v : a_s) + static_cast<size_t>(g) * n;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int i = blockIdx.x * 1024 + 256 * u + tid;
+        if (i < n) x[i] = expf(x[i] - m) * inv;
+    }
 }
 
 struct IndexerWs {
-    size_t hi_off, lo_off, total;
+    size_t hi_off, lo_off, part_off, total;
+    int nblk;
 };
 
-IndexerWs indexer_ws_layout(int d_h) {
+IndexerWs indexer_ws_layout(int kv_heads, int64_t n, int d_h) {
     IndexerWs w;
     w.hi_off = 0;
     w.lo_off = vs::round_up(static_cast<size_t>(d_h) * 256 * 2, 256);
-    w.total = 2 * w.lo_off;
+    w.part_off = 2 * w.lo_off;
+    w.nblk = static_cast<int>((n + kTokensPerWg - 1) / kTokensPerWg);
+    w.total = w.part_off + vs::round_up(static_cast<size_t>(kv_heads) * 2 * w.nblk * sizeof(float2), 256);
     return w;
 }
 
@@ -213,7 +267,7 @@ extern "C" {
 
 size_t vs_index_score_workspace(int kv_heads, int64_t n, int d_h) {
     if (kv_heads <= 0 || n <= 0 || !dh_supported(d_h)) return 0;
-    return indexer_ws_layout(d_h).total;
+    return indexer_ws_layout(kv_heads, n, d_h).total;
 }
 
 int vs_index_score(const void* k_bf16, const void* v_bf16, int kv_heads, int64_t n, const vs_indexer_t* w, float* a_v,
@@ -224,7 +278,7 @@ int vs_index_score(const void* k_bf16, const void* v_bf16, int kv_heads, int64_t
     if (kv_heads <= 0 || n <= 0) return VS_ERR_INVALID_ARG;
     if (w->act != 0 && w->act != 1) return VS_ERR_INVALID_ARG;
     if (!dh_supported(w->d_h) || n > VS_MAX_SEQ || kv_heads > 65535) return VS_ERR_UNSUPPORTED;
-    const IndexerWs lay = indexer_ws_layout(w->d_h);
+    const IndexerWs lay = indexer_ws_layout(kv_heads, n, w->d_h);
     if (!ws || ws_bytes < lay.total) return VS_ERR_WORKSPACE;
     if (!vs::aligned16(ws)) return VS_ERR_INVALID_ARG;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -241,20 +295,23 @@ int vs_index_score(const void* k_bf16, const void* v_bf16, int kv_heads, int64_t
     }
     hipLaunchKernelGGL(split_weights_kernel, dim3((w->d_h * 256 + 255) / 256), dim3(256), 0, st, w->W_U, w->d_h, hi, lo);
     VS_LAUNCH_CHECK();
-    const dim3 grid(static_cast<unsigned>((n + kTokensPerWg - 1) / kTokensPerWg), kv_heads);
-    // LDS: one 64-unit chunk of both weight halves + the three per-unit vectors; small enough at d_h = 256 for two
-    // workgroups per CU
-    const size_t smem = 2 * kChunkU * kWRowBytes + 3 * static_cast<size_t>(w->d_h) * 4;
+    float2* part = reinterpret_cast<float2*>(static_cast<unsigned char*>(ws) + lay.part_off);
+    // one workgroup per block of 256 tokens
+    const dim3 grid(static_cast<unsigned>(lay.nblk), kv_heads);
+    // LDS: one 64-unit chunk of both weight halves + the three per-unit vectors + 16 floats; small enough at d_h = 256
+    // for two workgroups per CU
+    const size_t smem = 2 * kChunkU * kWRowBytes + 3 * static_cast<size_t>(w->d_h) * 4 + 64;
     const uint16_t* kx = static_cast<const uint16_t*>(k_bf16);
     const uint16_t* vx = static_cast<const uint16_t*>(v_bf16);
     if (w->act == 0)
         hipLaunchKernelGGL(indexer_logits_kernel<0>, grid, dim3(kThreads), smem, st, kx, vx, static_cast<int>(n), w->d_h,
-                           hi, lo, w->b_U, w->W_V, w->W_S, w->b_V, w->b_S, a_v, a_s);
+                           hi, lo, w->b_U, w->W_V, w->W_S, w->b_V, w->b_S, a_v, a_s, part, lay.nblk);
     else
         hipLaunchKernelGGL(indexer_logits_kernel<1>, grid, dim3(kThreads), smem, st, kx, vx, static_cast<int>(n), w->d_h,
-                           hi, lo, w->b_U, w->W_V, w->W_S, w->b_V, w->b_S, a_v, a_s);
+                           hi, lo, w->b_U, w->W_V, w->W_S, w->b_V, w->b_S, a_v, a_s, part, lay.nblk);
     VS_LAUNCH_CHECK();
-    hipLaunchKernelGGL(softmax_rows_kernel, dim3(kv_heads, 2), dim3(1024), 0, st, a_v, a_s, static_cast<int>(n));
+    hipLaunchKernelGGL(softmax_finish_kernel, dim3(static_cast<unsigned>((n + 1023) / 1024), kv_heads, 2), dim3(256), 0, st, a_v,
+                       a_s, static_cast<int>(n), part, lay.nblk);
     VS_LAUNCH_CHECK();
     return VS_OK;
 }
