@@ -35,7 +35,8 @@ def test_strerror_and_workspace_queries():
         assert L.vs_strerror(code) not in (b"ok", b"unknown status")
     assert vs.sparse_prefill_workspace(32, 8, 8, 131072) > 3 * 8 * 131072 // 8 // 2
     assert vs.sparse_prefill_workspace(32, 8, 5, 131072) == 0          # index_heads must be q_heads or kv_heads
-    assert vs.index_score_workspace(8, 131072, 256) == 2 * 256 * 256 * 2
+    # two bf16 halves of W_U + one (max, sum) pair per head, direction and block of 256 tokens
+    assert vs.index_score_workspace(8, 131072, 256) == 2 * 256 * 256 * 2 + 8 * 2 * 512 * 8
     assert vs.index_score_workspace(8, 131072, 100) == 0               # d_h must be a multiple of 64
     assert vs.select_budget_workspace(8, 131072) == 0
 
