@@ -169,10 +169,6 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     int* const wtot = reinterpret_cast<int*>(smem + kScratchOff);
     int* const glist = reinterpret_cast<int*>(smem + kGatherOff);
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int qi = lane & 31, hh = lane >> 5;
     const float NEG_INF = -INFINITY;
 
     // ---- which tile ----
@@ -187,6 +183,13 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     int bid = blockIdx.x;
     for (;;) {
     if (bid >= p.work_total) break;
+    // The thread number is made opaque once per unit: every per-thread constant below is then recomputed per unit
+    // instead of being carried (and spilled) across the register-hungry loops of the previous unit.
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int qi = lane & 31, hh = lane >> 5;
     const int rest = bid / p.kv_heads;
     const int g = DENSE ? bid % p.kv_heads : (bid + rest) % p.kv_heads;
     const int hchunks = p.group / p.hc;
