@@ -24,7 +24,7 @@ constexpr int kTokensPerWg = 256;          // 4 wavefronts x 2 blocks of 32 toke
 constexpr int kChunkU = 64;                // hidden units staged in LDS at a time
 constexpr int kWRowBytes = 512 + 32;       // 256 bf16 + pad (conflict-free 16-byte fragment reads)
 constexpr int kMaxDh = 1024;
-constexpr size_t kSmemBytes = 2 * kChunkU * kWRowBytes + 3 * kMaxDh * 4 + 64;
+constexpr size_t kSmemBytes = 2 * kChunkU * kWRowBytes + 3 * kMaxDh * 4;
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
     uint32_t u = __float_as_uint(f);
@@ -88,7 +88,7 @@ __global__ __launch_bounds__(kThreads) void indexer_logits_kernel(const uint16_t
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, hh = lane >> 5;
     const int g = blockIdx.y;
-    float* const red = sWS + d_h;                          // 4 wavefronts x (max_v, sum_v, max_s, sum_s)
+    float* const red = reinterpret_cast<float*>(smem);     // 4 wavefronts x (max_v, sum_v, max_s, sum_s); over the weight chunk, after its last use
 
     for (int u = tid; u < d_h; u += kThreads) {
         sbU[u] = b_U[u];
@@ -193,6 +193,7 @@ __global__ __launch_bounds__(kThreads) void indexer_logits_kernel(const uint16_t
         ev += __shfl_xor(ev, d);
         es += __shfl_xor(es, d);
     }
+    __syncthreads();                                        // every wavefront is done with the weight chunk
     if (lane == 0) {
         red[4 * wave] = mv;
         red[4 * wave + 1] = ev;
@@ -298,9 +299,8 @@ int vs_index_score(const void* k_bf16, const void* v_bf16, int kv_heads, int64_t
     float2* part = reinterpret_cast<float2*>(static_cast<unsigned char*>(ws) + lay.part_off);
     // one workgroup per block of 256 tokens
     const dim3 grid(static_cast<unsigned>(lay.nblk), kv_heads);
-    // LDS: one 64-unit chunk of both weight halves + the three per-unit vectors + 16 floats; small enough at d_h = 256
-    // for two workgroups per CU
-    const size_t smem = 2 * kChunkU * kWRowBytes + 3 * static_cast<size_t>(w->d_h) * 4 + 64;
+    // LDS: one 64-unit chunk of both weight halves + the three per-unit vectors; two workgroups per CU up to d_h = 1024
+    const size_t smem = 2 * kChunkU * kWRowBytes + 3 * static_cast<size_t>(w->d_h) * 4;
     const uint16_t* kx = static_cast<const uint16_t*>(k_bf16);
     const uint16_t* vx = static_cast<const uint16_t*>(v_bf16);
     if (w->act == 0)
