@@ -36,6 +36,7 @@ struct SelShared {
     uint32_t hist_cnt[kMaxBuckets];
     u64 wave_m[kWaves];
     uint32_t wave_c[kWaves];
+    uint32_t wave_eq[kWaves], wave_eqf[kWaves], wave_in[kWaves];   // emission: ties, forced ties, entries in without a tie
     // result of the bucket search
     uint32_t sel_bucket, eq_c;
     u64 above_m, eq_m;
@@ -60,12 +61,6 @@ __device__ __forceinline__ u64 key_mass(uint32_t key, int& st) {
     return static_cast<u64>(xd * 1099511627776.0);   // exact power-of-two scaling, truncation
 }
 
-__device__ __forceinline__ u64 wave_sum(u64 x) {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) x += __shfl_xor(x, d);
-    return x;
-}
-
 // Selection state of one (head, direction): elements with key > vstar are in; of those with
 // key == vstar the first `ties` in index order are in.  none: nothing is selected by rank.
 struct Pick {
@@ -85,10 +80,13 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelParams p) 
     int st = 0;
     if (tid == 0) sh.status = 0;
 
-    // radix descent.  by_count: rank target is a count (krem) instead of a mass (trem).
-    auto descend = [&](bool by_count, bool skip_forced, u64 trem, uint32_t krem) -> Pick {
+    // radix descent.  by_count: rank target is a count (krem) instead of a mass (trem).  tau >= 0 (first descent of the
+    // threshold rule): the first pass sees every element, so its histogram also gives the total mass; the target
+    // ceil(tau * total) is taken from it instead of from a sweep of its own.  first: the first pass also collects the
+    // status bits of the scores.
+    auto descend = [&](bool by_count, bool skip_forced, u64 trem, uint32_t krem, double tau, bool first) -> Pick {
         Pick pk{0u, 0u, false};
-        if (by_count ? krem == 0 : trem == 0) {
+        if (tau < 0.0 && (by_count ? krem == 0 : trem == 0)) {
             pk.none = true;
             return pk;
         }
@@ -102,14 +100,16 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelParams p) 
                 sh.hist_cnt[b] = 0;
             }
             __syncthreads();
+            const bool collect = first && pass == 0;
             for (int i = tid; i < n; i += kSelThreads) {
                 if (skip_forced && i < nforced) continue;
                 int dummy = 0;
-                const uint32_t key = score_key(a[i], dummy);
+                const uint32_t key = score_key(a[i], collect ? st : dummy);
                 if ((key & pmask) != prefix) continue;
                 const uint32_t b = (key >> shf) & (nb - 1);
                 atomicAdd(&sh.hist_cnt[b], 1u);
-                if (!by_count) atomicAdd(&sh.hist_mass[b], key_mass(key, dummy));
+                if (!by_count) atomicAdd(&sh.hist_mass[b], key_mass(key, collect ? st : dummy));
+                else if (collect) (void)key_mass(key, st);
             }
             __syncthreads();
             // buckets in descending order; thread owns `per` consecutive ones
@@ -151,6 +151,16 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelParams p) 
                 mbase += sh.wave_m[w];
                 cbase += sh.wave_c[w];
             }
+            if (pass == 0 && tau >= 0.0) {
+                u64 total = 0;
+                for (int w = 0; w < kWaves; ++w) total += sh.wave_m[w];
+                trem = static_cast<u64>(ceil(tau * static_cast<double>(total)));
+                if (trem == 0) {                              // uniform: every thread sees the same total
+                    pk.none = true;
+                    __syncthreads();
+                    return pk;
+                }
+            }
             u64 mrun = mbase + mi - msum;
             uint32_t crun = cbase + ci - csum;
 #pragma unroll
@@ -190,23 +200,16 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelParams p) 
     // ---- total mass, threshold ----
     Pick pk;
     if (p.mode == 0) {
-        u64 s = 0;
-        for (int i = tid; i < n; i += kSelThreads) s += key_mass(score_key(a[i], st), st);
-        s = wave_sum(s);
-        if (lane == 0) sh.wave_m[wave] = s;
-        __syncthreads();
-        u64 total = 0;
-        for (int w = 0; w < kWaves; ++w) total += sh.wave_m[w];
-        __syncthreads();
-        const double prod = p.tau[dir] * static_cast<double>(total);
-        const u64 target = static_cast<u64>(ceil(prod));
-        pk = descend(false, false, target, 0u);
+        pk = descend(false, false, 0, 0u, p.tau[dir], true);
     } else {
-        for (int i = tid; i < n; i += kSelThreads) {
-            const uint32_t key = score_key(a[i], st);
-            (void)key_mass(key, st);
+        const uint32_t kfix = static_cast<uint32_t>(min(p.kfix[dir], n));
+        if (kfix == 0) {                                     // nothing ranked in: the status bits still need their sweep
+            for (int i = tid; i < n; i += kSelThreads) {
+                const uint32_t key = score_key(a[i], st);
+                (void)key_mass(key, st);
+            }
         }
-        pk = descend(true, false, 0, static_cast<uint32_t>(min(p.kfix[dir], n)));
+        pk = descend(true, false, 0, kfix, -1.0, true);
     }
 
     // ---- ordered emission: each wavefront owns a contiguous range, ranks come from ballots ----
@@ -217,20 +220,46 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelParams p) 
 
     bool skip_forced = false;
     for (int attempt = 0; attempt < 2; ++attempt) {
-        // sweep 1: ties per wavefront
-        uint32_t eqc = 0;
+        // sweep 1: per wavefront, the ties, the ties among the forced entries, and the entries that are in whatever the
+        // ties decide (forced, or ranked above the crossing value).  Ties are taken in index order and the forced entries
+        // are the lowest indices, so the number of selected entries of a wavefront follows from these three counts.
+        uint32_t eqc = 0, eqf = 0, inc = 0;
         for (int base = w_lo; base < w_hi; base += 64) {
             const int i = base + lane;
-            int dummy = 0;
-            const bool eq = i < w_hi && !pk.none && !(skip_forced && i < nforced) && score_key(a[i], dummy) == pk.vstar;
+            bool eq = false, in = false, forced = false;
+            if (i < w_hi) {
+                int dummy = 0;
+                const uint32_t key = score_key(a[i], dummy);
+                forced = i < nforced;
+                const bool ranked = !pk.none && !(skip_forced && forced);
+                eq = ranked && key == pk.vstar;
+                in = forced || (ranked && key > pk.vstar);
+            }
             eqc += __popcll(__ballot(eq));
+            eqf += __popcll(__ballot(eq && forced));
+            inc += __popcll(__ballot(in));
         }
-        if (lane == 0) sh.wave_c[wave] = eqc;
+        if (lane == 0) {
+            sh.wave_eq[wave] = eqc;
+            sh.wave_eqf[wave] = eqf;
+            sh.wave_in[wave] = inc;
+        }
         __syncthreads();
-        uint32_t tie_base = 0;
-        for (int w = 0; w < wave; ++w) tie_base += sh.wave_c[w];
+        uint32_t tie_base = 0, pos = 0, total = 0;
+        {
+            uint32_t ties_before = 0;
+            for (int w = 0; w < kWaves; ++w) {
+                const uint32_t e = sh.wave_eq[w], ef = sh.wave_eqf[w];
+                // free ties of wavefront w that are taken: its forced ties come first and are already counted as in
+                const uint32_t room = pk.ties > ties_before + ef ? pk.ties - ties_before - ef : 0u;
+                const uint32_t sel = sh.wave_in[w] + min(room, e - ef);
+                if (w < wave) pos += sel;
+                if (w == wave) tie_base = ties_before;
+                total += sel;
+                ties_before += e;
+            }
+        }
         __syncthreads();
-        // sweep 2: selected per wavefront
         auto selected = [&](int i, uint32_t& tie_run) -> bool {
             bool in = false, eq = false;
             if (i < w_hi) {
@@ -246,24 +275,15 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelParams p) 
             tie_run += __popcll(eb);
             return in;
         };
-        uint32_t tie_run = tie_base, selc = 0;
-        for (int base = w_lo; base < w_hi; base += 64) selc += __popcll(__ballot(selected(base + lane, tie_run)));
-        if (lane == 0) sh.wave_c[wave] = selc;
-        __syncthreads();
-        uint32_t pos = 0, total = 0;
-        for (int w = 0; w < kWaves; ++w) {
-            if (w < wave) pos += sh.wave_c[w];
-            total += sh.wave_c[w];
-        }
-        __syncthreads();
+        uint32_t tie_run = tie_base;
         if (total > static_cast<uint32_t>(cap) && attempt == 0) {
             // keep the forced entries and the best-ranked others: count-ranked pick over the rest
             st |= VS_STATUS_OVERFLOW;
             skip_forced = true;
-            pk = descend(true, true, 0, static_cast<uint32_t>(cap - nforced));
+            pk = descend(true, true, 0, static_cast<uint32_t>(cap - nforced), -1.0, false);
             continue;
         }
-        // sweep 3: write
+        // sweep 2: write
         tie_run = tie_base;
         for (int base = w_lo; base < w_hi; base += 64) {
             const bool in = selected(base + lane, tie_run);
