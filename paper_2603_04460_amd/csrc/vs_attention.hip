@@ -98,7 +98,7 @@ struct AttnParams {
     const int32_t* ncol32;          // per index head and 32-row block q: number of listed columns <= 32 q + 31
     int nq32;                       // entries per head of ncol32
     unsigned long long* tile_counter;
-    unsigned int* work_counter;     // persistent launch: next unit of work (zero at launch); null: one unit per workgroup
+    unsigned int* work_counter;     // persistent launch: next unit of every KV head's queue (zero at launch); null: one unit per workgroup
     int work_total;                 // units of work (query tiles x KV heads x head chunks)
 };
 
@@ -175,13 +175,42 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     // Workgroups are dealt to the 8 XCDs round-robin.  Dense: KV head = bid % kv_heads keeps a head's K / V in one
     // XCD's L2 (every head has the same work).  Sparse: heads differ in budget, so the head rotates with the tile
     // index and every XCD gets an equal share of every head.
-    // Persistent launch (sparse): one workgroup per compute unit takes units from a counter until none is left.  The
+    // Persistent launch (sparse): one workgroup per compute unit takes units from counters until none is left.  The
     // hardware dispatcher left a compute unit idle for ~20 us between two of these 160 KB / 512-thread workgroups
-    // (measured: 23 % of the kernel at 128k), and a unit of work lasts only ~90 us.
-    // The first unit is the workgroup's own index, later ones come from the counter (claiming the next unit early, to
-    // hide the counter's round trip, measured no faster).  Every wavefront leaves the loop at the same unit number.
+    // (measured: 23 % of the kernel at 128k), and a unit of work lasts only ~90 us.  Claiming the next unit early, to
+    // hide the counter's round trip, measured no faster.  Every wavefront leaves the loop at the same point.
+    // Sparse, persistent: one queue of units per KV head (counters in the workspace).  A workgroup starts in the queue
+    // of head (its XCD number) % kv_heads, so an XCD's L2 mostly sees one head's K / V, and moves on to the next
+    // queue when its own is empty: no head can become the critical path.
     int bid = blockIdx.x;
+    int queue = 0;
+    const int units_per_head = p.work_total / p.kv_heads;
+    if (!DENSE && p.work_counter) {
+        queue = static_cast<int>(__builtin_amdgcn_s_getreg((20) | (0 << 6) | (3 << 11)) & 0xf) % p.kv_heads;   // XCC_ID
+        bid = -1;
+    }
     for (;;) {
+    if (!DENSE && p.work_counter) {
+        __syncthreads();                                     // LDS and the slots below are free again
+        if (threadIdx.x == 0) {
+            int q = queue, unit = -1;
+            for (int t = 0; t < p.kv_heads; ++t) {
+                const int u = static_cast<int>(atomicAdd(p.work_counter + q, 1u));
+                if (u < units_per_head) {
+                    unit = u;
+                    break;
+                }
+                q = q + 1 == p.kv_heads ? 0 : q + 1;
+            }
+            wtot[31] = unit;
+            wtot[30] = q;
+        }
+        __syncthreads();
+        queue = __builtin_amdgcn_readfirstlane(wtot[30]);
+        const int unit = __builtin_amdgcn_readfirstlane(wtot[31]);
+        if (unit < 0) break;
+        bid = unit * p.kv_heads;                             // rest = unit; the head comes from the queue
+    }
     if (bid >= p.work_total) break;
     // The thread number is made opaque once per unit: every per-thread constant below is then recomputed per unit
     // instead of being carried (and spilled) across the register-hungry loops of the previous unit.
@@ -191,7 +220,7 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int qi = lane & 31, hh = lane >> 5;
     const int rest = bid / p.kv_heads;
-    const int g = DENSE ? bid % p.kv_heads : (bid + rest) % p.kv_heads;
+    const int g = DENSE ? bid % p.kv_heads : (p.work_counter ? queue : (bid + rest) % p.kv_heads);
     const int hchunks = p.group / p.hc;
     const int hchunk = rest % hchunks;
     const int tile = p.tiles - 1 - rest / hchunks;          // longest tiles first
@@ -715,10 +744,6 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     }
     if (p.tile_counter && lane == 0 && tiles_done) atomicAdd(p.tile_counter, static_cast<unsigned long long>(tiles_done));
     if (!p.work_counter) break;
-    __syncthreads();                                         // LDS and the slot below are free again
-    if (tid == 0) wtot[31] = static_cast<int>(gridDim.x + atomicAdd(p.work_counter, 1u));
-    __syncthreads();
-    bid = __builtin_amdgcn_readfirstlane(wtot[31]);
     }
 }
 
@@ -899,7 +924,9 @@ int vs_sparse_prefill_tiled(const void* q, const void* k, const void* v, int q_h
     p.ncol32 = ncol32;
     p.nq32 = w.nq32;
     p.tile_counter = reinterpret_cast<unsigned long long*>(base + w.counter_off);
-    p.work_counter = reinterpret_cast<unsigned int*>(base + w.counter_off + 128);   // zeroed with the bitmaps above
+    // one queue counter per KV head at bytes 128.. of the counter block (zeroed with the bitmaps above); more than 32
+    // KV heads do not fit there: one workgroup per unit then
+    p.work_counter = kv_heads <= 32 ? reinterpret_cast<unsigned int*>(base + w.counter_off + 128) : nullptr;
     return launch_attention<false>(p, st);
 }
 
