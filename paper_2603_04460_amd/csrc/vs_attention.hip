@@ -171,17 +171,16 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
 
     const float NEG_INF = -INFINITY;
 
-    // ---- which tile ----
-    // Workgroups are dealt to the 8 XCDs round-robin.  Dense: KV head = bid % kv_heads keeps a head's K / V in one
-    // XCD's L2 (every head has the same work).  Sparse: heads differ in budget, so the head rotates with the tile
-    // index and every XCD gets an equal share of every head.
-    // Persistent launch (sparse): one workgroup per compute unit takes units from counters until none is left.  The
-    // hardware dispatcher left a compute unit idle for ~20 us between two of these 160 KB / 512-thread workgroups
-    // (measured: 23 % of the kernel at 128k), and a unit of work lasts only ~90 us.  Claiming the next unit early, to
-    // hide the counter's round trip, measured no faster.  Every wavefront leaves the loop at the same point.
-    // Sparse, persistent: one queue of units per KV head (counters in the workspace).  A workgroup starts in the queue
-    // of head (its XCD number) % kv_heads, so an XCD's L2 mostly sees one head's K / V, and moves on to the next
-    // queue when its own is empty: no head can become the critical path.
+    // ---- which unit of work: (query tile, KV head, chunk of the group's query heads) ----
+    // Dense: one workgroup per unit, longest tiles first; workgroups are dealt to the 8 XCDs round-robin, so
+    // KV head = bid % kv_heads keeps a head's K / V in one XCD's L2 (every head has the same work).
+    // Sparse: persistent launch, one workgroup per compute unit takes units from counters in the workspace until none
+    // is left.  With one workgroup per unit the hardware dispatcher left a compute unit idle for ~20 us between two of
+    // these 160 KB / 512-thread workgroups (measured: 23 % of the kernel at 128k; a unit lasts only ~90 us).  There is
+    // one queue of units per KV head.  A workgroup starts in the queue of head (its XCD number) % kv_heads, so an XCD's
+    // L2 mostly sees one head's K / V, and moves on to the next queue when its own is empty, so that heads with a
+    // larger budget do not become the critical path.  Every wavefront leaves the loop at the same point.  (Without
+    // counters, more than 32 KV heads: one workgroup per unit, heads rotated over the XCDs.)
     int bid = blockIdx.x;
     int queue = 0;
     const int units_per_head = p.work_total / p.kv_heads;
