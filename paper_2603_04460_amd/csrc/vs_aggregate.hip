@@ -213,7 +213,11 @@ __global__ __launch_bounds__(kThreads) void vs_sweep_kernel(const SweepParams p)
                     float pr = __builtin_amdgcn_exp2f(acc[4 * a + c] * p.c - nv[c]);
                     if (diag_tile && 8 * a + c < lim) pr = 0.f;
                     psum += pr;
-                    if (RECALL && ((keep >> (8 * a + c)) & 1u)) rsum += pr;
+                    if (RECALL) {                            // adds pr where the keep-bit is set: bit spread over a word, and, add
+                        uint32_t m;
+                        asm("v_bfe_i32 %0, %1, %2, 1" : "=v"(m) : "v"(keep), "n"(8 * a + c));
+                        rsum += __uint_as_float(__float_as_uint(pr) & m);
+                    }
                     const float rot = __int_as_float(__builtin_amdgcn_ds_bpermute(rot_src[4 * a + c], __float_as_int(pr)));
                     dsum += rot;
                     dwrap = fmaf(rot, rot_wrap[4 * a + c], dwrap);
