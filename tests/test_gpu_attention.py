@@ -111,6 +111,30 @@ def test_sparse_randomized_sweep():
                                  % (case, hq, hk, n, nv, ns, runs, per_q, gran, e))
 
 
+def test_workspace_reused_across_calls_of_different_size():
+    """One oversized workspace, a large call, then a small one, then the large one again: every call re-initialises
+    the counters and bitmaps it uses, so results do not depend on what the workspace held before."""
+    rng = np.random.default_rng(99)
+    hq, hk = 8, 2
+    ws = torch.empty(vs.sparse_prefill_workspace(hq, hk, hk, 4096) + 4096, dtype=torch.uint8, device="cuda")
+    ws.fill_(0xA5)
+    outs = []
+    for n in (1500, 300, 1500):
+        (q, k, v), (qb, kb, vb) = make_qkv(600 + n, hq, hk, n)
+        sv, ss = _random_sets(np.random.default_rng(n), n, hk, 60, 90)
+        iv, cv = lists(sv)
+        is_, cs = lists(ss)
+        f = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+        o = torch.full_like(q, float("nan"))
+        lse = torch.full((hq, n), float("nan"), dtype=torch.float32, device="cuda")
+        vs.sparse_prefill(q, k, v, f(iv), f(cv), f(is_), f(cs), o, lse, ws)
+        torch.cuda.synchronize()
+        ref_o, ref_lse = oracle.sparse_attention(qb, kb, vb, iv, cv, is_, cs)
+        check_attention(o, lse, ref_o, ref_lse)
+        outs.append(o.clone())
+    assert torch.equal(outs[0].view(torch.int16), outs[2].view(torch.int16))
+
+
 def test_sparse_edge_cases():
     n, hq, hk = 300, 4, 1
     (q, k, v), (qb, kb, vb) = make_qkv(7, hq, hk, n)
