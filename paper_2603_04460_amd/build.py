@@ -16,6 +16,11 @@ HIPCC_FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"),
 ]
+# per-source additions
+EXTRA_FLAGS = {
+    # one wavefront per SIMD with 512 registers: score accumulators go to the vector registers the softmax reads
+    "vs_dense.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+}
 
 
 def stale():
@@ -37,7 +42,7 @@ def build_library(force=True, verbose=False):
     for src in SOURCES:
         obj = os.path.join(bdir, os.path.basename(src) + ".o")
         objs.append(obj)
-        cmd = [hipcc] + HIPCC_FLAGS + ["-c", src, "-o", obj]
+        cmd = [hipcc] + HIPCC_FLAGS + EXTRA_FLAGS.get(os.path.basename(src), []) + ["-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd))
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))

@@ -1,4 +1,4 @@
-// Causal vertical-slash sparse attention and dense causal attention for gfx950.
+// Causal vertical-slash sparse attention for gfx950.
 //
 // One workgroup (8 wavefronts, two per SIMD) owns a query tile of one KV head: 8 row blocks of 32
 // query rows, arranged as hc query heads of the KV group times 8/hc consecutive 32-row sub-blocks
@@ -40,30 +40,13 @@
 
 #include <type_traits>
 
-#include "vs_common.h"
+#include "vs_attn_device.h"
 #include "vs_device.h"
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4t __attribute__((__vector_size__(4 * sizeof(__bf16))));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-constexpr int kD = 128;
 constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / 64;
-// A tile is staged with loads that write LDS directly: one wavefront instruction deposits its 64 16-byte pieces
-// back to back, which makes 4 rows of 256 B a contiguous 1 KB group.  Groups are 64 B apart and the pieces are rotated
-// inside a group so that fragment reads spread over all banks:
-//   K (16-byte reads, 16 rows at one chunk c): chunk c of row r sits at 64 (c / 4) + 16 ((c + r) % 4) of its row
-//   V (transposing reads, 4 rows x 64 B):      byte x of row r sits at 64 ((x / 64 + r) % 4) + x % 64 of its row
-constexpr int kGroupBytes = 4 * 256 + 64;      // four rows and the gap to the next group
-constexpr int kTileBytes = 8 * kGroupBytes;    // one 32-key tile of K or V
-constexpr int kSlotBytes = 2 * kTileBytes;     // one LDS slot: a K tile, then the V tile of the same keys
-constexpr int kSlots = 6;                      // ring of three stages of two tiles
 constexpr int kListCap = 2048;                 // block list: kListCap / nsub entries per round
 constexpr int kGatherCap = 4096;               // entries of the per-round gather list
 constexpr int kTbitWords = 1024;               // touched-block bits for up to 32768 key blocks (n <= 2^20)
@@ -76,89 +59,7 @@ constexpr size_t kScratchOff = kTbitOff + kTbitWords * 4;
 constexpr size_t kGatherOff = kScratchOff + 128;
 constexpr size_t kSmemBytes = kGatherOff + kGatherCap * 4;
 static_assert(kSmemBytes <= 160 * 1024, "LDS of one compute unit");
-constexpr uint64_t kAll63 = 0x7fffffffffffffffull;
-constexpr float kRescaleThreshold = 8.0f;      // log2 units: stale maxima up to 2^8 are tolerated
 
-struct AttnParams {
-    const uint16_t* q;
-    const uint16_t* k;
-    const uint16_t* v;
-    uint16_t* o;
-    float* lse;
-    int q_heads, kv_heads, group, hc, n, tiles, index_per_q;
-    int gran;                       // slash granularity: 1 (element-exact) or 32 (per 32-row block)
-    float scale, c;                 // c = scale * log2(e)
-    const int32_t* idx_v;
-    const int32_t* cnt_v;
-    int cap_v;
-    const uint32_t* sbit;           // per index head: bit (o + 64) set iff offset o selected
-    const uint32_t* vbit;           // per index head: bit j set iff column j selected
-    const uint32_t* t32;            // per index head: bit t set iff an offset in [32t-31, 32t+31] is selected
-    int sw, vw, tw;                 // words per head of the three bitmaps
-    const int32_t* ncol32;          // per index head and 32-row block q: number of listed columns <= 32 q + 31
-    int nq32;                       // entries per head of ncol32
-    unsigned long long* tile_counter;
-    unsigned int* work_counter;     // persistent launch: next unit of every KV head's queue (zero at launch); null: one unit per workgroup
-    int work_total;                 // units of work (query tiles x KV heads x head chunks)
-};
-
-__device__ __forceinline__ float half_swap_max(float x) {
-    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-
-__device__ __forceinline__ float half_swap_sum(float x) {
-    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
-__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-}
-
-__device__ __forceinline__ uint64_t uniform64(uint64_t x) {
-    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(x));
-    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(x >> 32));
-    return (static_cast<uint64_t>(hi) << 32) | lo;
-}
-
-// Keep-bits of one lane of a 32x32 S^T tile.  Lane (q, h) holds, in accumulator element E = 4a + c, key kj = 8a + 4h + c
-// of query q; the result has that element's keep-bit at position 27 - 8a - c.
-// w: selected offsets dlt-31 .. dlt+31 at bits 0..62 (key kj of row q is offset bit 31 + q - kj); cz: the causal ones
-// among them; vw: selected columns of the block.  sh = q + 4 - 4h and ysh = 4 - 4h are per-lane constants.
-__device__ __forceinline__ uint32_t lane_keep_bits(uint64_t w, uint64_t cz, uint32_t vw, int sh, int ysh) {
-    const uint32_t x = static_cast<uint32_t>(w >> sh), cx = static_cast<uint32_t>(cz >> sh);
-    const uint32_t y = __builtin_bitreverse32(vw) >> ysh;   // bit 27 - 8a - c = column 8a + 4h + c
-    return x | (y & cx);
-}
-
-// Four elements (one group a) at a time: the keep-bits spread over a word each (written out: from the C form the compiler
-// makes and + compare + select), then a bitwise select that stays visible to the compiler, which must space it from the
-// matrix instruction that produced acc.
-template <int A>
-__device__ __forceinline__ void mask_elements(f32x16& acc, uint32_t keep, uint32_t dead_bits) {
-    uint32_t m0, m1, m2, m3;
-    asm("v_bfe_i32 %0, %4, %5, 1\n\tv_bfe_i32 %1, %4, %6, 1\n\tv_bfe_i32 %2, %4, %7, 1\n\tv_bfe_i32 %3, %4, %8, 1"
-        : "=&v"(m0), "=&v"(m1), "=&v"(m2), "=&v"(m3)
-        : "v"(keep), "n"(27 - 8 * A), "n"(26 - 8 * A), "n"(25 - 8 * A), "n"(24 - 8 * A));
-    acc[4 * A] = __uint_as_float((m0 & __float_as_uint(acc[4 * A])) | (~m0 & dead_bits));
-    acc[4 * A + 1] = __uint_as_float((m1 & __float_as_uint(acc[4 * A + 1])) | (~m1 & dead_bits));
-    acc[4 * A + 2] = __uint_as_float((m2 & __float_as_uint(acc[4 * A + 2])) | (~m2 & dead_bits));
-    acc[4 * A + 3] = __uint_as_float((m3 & __float_as_uint(acc[4 * A + 3])) | (~m3 & dead_bits));
-    if constexpr (A + 1 < 4) mask_elements<A + 1>(acc, keep, dead_bits);
-}
-
-// 16 bytes per lane from global memory straight into LDS: lane L's piece lands at lds_base + 16 L (lds_base is
-// wave-uniform).  Written as an instruction rather than through the builtin: the compiler orders every later LDS read
-// behind a builtin load it cannot tell apart (a full vmcnt wait in the middle of the pipeline); here the kernel itself
-// waits (vmcnt) before the barrier that publishes a stage.
-__device__ __forceinline__ void lds_load16(const void* gsrc, const void* lds_base) {
-    const uint32_t base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
-        (const __attribute__((address_space(3))) void*)lds_base));
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(base), "v"(gsrc) : "memory", "m0");
-}
-
-template <bool DENSE>
 __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams p) {
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char* const kvbuf = smem;
@@ -172,10 +73,7 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     const float NEG_INF = -INFINITY;
 
     // ---- which unit of work: (query tile, KV head, chunk of the group's query heads) ----
-    // Dense: one workgroup per unit, longest tiles first; workgroups are dealt to the 8 XCDs round-robin, so
-    // KV head = bid % kv_heads keeps a head's K / V in one XCD's L2 (every head has the same work).
-    // Sparse: persistent launch, one workgroup per compute unit takes units from counters in the workspace until none
-    // is left.  With one workgroup per unit the hardware dispatcher left a compute unit idle for ~20 us between two of
+    // Persistent launch: one workgroup per compute unit takes units from counters in the workspace until none is left.  With one workgroup per unit the hardware dispatcher left a compute unit idle for ~20 us between two of
     // these 160 KB / 512-thread workgroups (measured: 23 % of the kernel at 128k; a unit lasts only ~90 us).  There is
     // one queue of units per KV head.  A workgroup starts in the queue of head (its XCD number) % kv_heads, so an XCD's
     // L2 mostly sees one head's K / V, and moves on to the next queue when its own is empty, so that heads with a
@@ -184,12 +82,12 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     int bid = blockIdx.x;
     int queue = 0;
     const int units_per_head = p.work_total / p.kv_heads;
-    if (!DENSE && p.work_counter) {
+    if (p.work_counter) {
         queue = static_cast<int>(__builtin_amdgcn_s_getreg((20) | (0 << 6) | (3 << 11)) & 0xf) % p.kv_heads;   // XCC_ID
         bid = -1;
     }
     for (;;) {
-    if (!DENSE && p.work_counter) {
+    if (p.work_counter) {
         __syncthreads();                                     // LDS and the slots below are free again
         if (threadIdx.x == 0) {
             int q = queue, unit = -1;
@@ -219,7 +117,7 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int qi = lane & 31, hh = lane >> 5;
     const int rest = bid / p.kv_heads;
-    const int g = DENSE ? bid % p.kv_heads : (p.work_counter ? queue : (bid + rest) % p.kv_heads);
+    const int g = p.work_counter ? queue : (bid + rest) % p.kv_heads;
     const int hchunks = p.group / p.hc;
     const int hchunk = rest % hchunks;
     const int tile = p.tiles - 1 - rest / hchunks;          // longest tiles first
@@ -234,9 +132,9 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     const int my_i0 = i0 + 32 * (wave / p.hc);
     const bool my_rows = my_i0 < n;
     const int ih = p.index_per_q ? my_head : g;
-    const uint32_t* __restrict__ sbit = DENSE ? nullptr : p.sbit + static_cast<size_t>(ih) * p.sw;
-    const uint32_t* __restrict__ vbit = DENSE ? nullptr : p.vbit + static_cast<size_t>(ih) * p.vw;
-    const uint32_t* __restrict__ t32 = DENSE ? nullptr : p.t32 + static_cast<size_t>(ih) * p.tw;
+    const uint32_t* __restrict__ sbit = p.sbit + static_cast<size_t>(ih) * p.sw;
+    const uint32_t* __restrict__ vbit = p.vbit + static_cast<size_t>(ih) * p.vw;
+    const uint32_t* __restrict__ t32 = p.t32 + static_cast<size_t>(ih) * p.tw;
 
     const uint16_t* __restrict__ kbase = p.k + static_cast<size_t>(g) * n * kD;
     const uint16_t* __restrict__ vbase = p.v + static_cast<size_t>(g) * n * kD;
@@ -361,17 +259,17 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     };
     const int bcap = kListCap / nsub;                        // listed blocks per round
     const int my_sub = wave / p.hc;
-    // t: position in the block list (sparse) or the block number itself (dense)
+    // t: position in the block list
     auto block_info = [&](int t) __attribute__((always_inline)) -> TileInfo {
         TileInfo ti{false, false, 0ull, 0ull, 0u, nullptr};
-        const int b = DENSE ? t : __builtin_amdgcn_readfirstlane(list[t]);
+        const int b = __builtin_amdgcn_readfirstlane(list[t]);
         const int dlt = my_i0 - 32 * b;                      // offset of (row 0, key 0) of the 32x32 tile
         if (dlt < -31 || !my_rows) return ti;                // every key lies after every row / padding rows
         ti.cz = dlt >= 31 ? kAll63 : ((kAll63 << (31 - dlt)) & kAll63);   // offsets >= 0
         // selected offsets dlt-31 .. dlt+31 at bits 0..62 and the block's column word, both prepared with the list
-        ti.w = DENSE ? ti.cz : uniform64(list_w[my_sub * bcap + t]);
-        ti.vw = DENSE ? 0u : static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(list_vw[t]));
-        if (!DENSE && p.gran == 32) {
+        ti.w = uniform64(list_w[my_sub * bcap + t]);
+        ti.vw = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(list_vw[t]));
+        if (p.gran == 32) {
             // Tile-granular slash: key kj is kept for every causal row of this 32-row block if ANY of its rows reaches it
             // through a selected offset, i.e. if the window has a bit in [31 - kj, 62 - kj].  That is exactly how a
             // selected column behaves inside the tile, so the keys join the column word and the offset window is dropped.
@@ -420,7 +318,7 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     };
 
     // ---- pipeline over the tiles of one phase ----
-    // GATHER == false: tile t is key block (DENSE ? t : list[t]);  GATHER == true: tile t is glist[32 t .. 32 t + 31].
+    // GATHER == false: tile t is key block list[t];  GATHER == true: tile t is glist[32 t .. 32 t + 31].
     // A stage is two tiles (64 keys).  Three stages live in LDS: step s computes on stage s, prefetches K fragments of
     // stage s+1 (complete since the last barrier) and refills the buffer of stage s-1 with stage s+2, whose global loads
     // were started at the top of the step.  One barrier per step.  The two tiles of a stage go through one softmax
@@ -437,7 +335,7 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
                 // loads need no predicate
                 int row = 0;
                 if (t < ntiles) {
-                    row = GATHER ? glist[32 * t + st_row] : 32 * (DENSE ? t : list[t]) + st_row;
+                    row = GATHER ? glist[32 * t + st_row] : 32 * list[t] + st_row;
                     if (row >= n) row = 0;
                 }
                 rows[u] = row;
@@ -489,34 +387,17 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
             f32x16 s0, s1;
 #pragma unroll
             for (int e = 0; e < 16; ++e) s0[e] = s1[e] = 0.f;
-            if (DENSE) {
-                // both tiles are live almost always: two independent accumulation chains, issued alternately
-                if (b.live) read_k(2 * buf + 1, k1);
-                if (a.live && b.live) {
-                    tiles_done += 2;
+            // one chain after the other; the second tile's fragments are requested before the first chain starts
+            if (b.live) read_k(2 * buf + 1, k1);
+            if (a.live) {
+                ++tiles_done;
 #pragma unroll
-                    for (int kk = 0; kk < 8; ++kk) {
-                        s0 = mfma32(k0[kk], qf[kk], s0);
-                        s1 = mfma32(k1[kk], qf[kk], s1);
-                    }
-                } else if (a.live) {
-                    ++tiles_done;
+                for (int kk = 0; kk < 8; ++kk) s0 = mfma32(k0[kk], qf[kk], s0);
+            }
+            if (b.live) {
+                ++tiles_done;
 #pragma unroll
-                    for (int kk = 0; kk < 8; ++kk) s0 = mfma32(k0[kk], qf[kk], s0);
-                }
-            } else {
-                // one chain after the other; the second tile's fragments are requested before the first chain starts
-                if (b.live) read_k(2 * buf + 1, k1);
-                if (a.live) {
-                    ++tiles_done;
-#pragma unroll
-                    for (int kk = 0; kk < 8; ++kk) s0 = mfma32(k0[kk], qf[kk], s0);
-                }
-                if (b.live) {
-                    ++tiles_done;
-#pragma unroll
-                    for (int kk = 0; kk < 8; ++kk) s1 = mfma32(k1[kk], qf[kk], s1);
-                }
+                for (int kk = 0; kk < 8; ++kk) s1 = mfma32(k1[kk], qf[kk], s1);
             }
             if (na.live) read_k(2 * buf1, k0);               // first tile of the next stage: in LDS since the last barrier
             if (a.live || b.live) {
@@ -564,9 +445,7 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
 
     // ---- phases ----
     const int nblk = i_last / 32 + 1;                       // key blocks that hold causal keys for this tile
-    if (DENSE) {
-        run_phase(nblk, std::false_type{});
-    } else {
+    {
         // 1. blocks crossed by a selected diagonal for any 32-row sub-block of the tile, one 32-block word per thread:
         //    block b = 32 W + j is crossed by sub-block r iff T32 bit (qb0 + r - b) is set, so the word is the
         //    bit-reversed 32-bit window of T32 that ends at qb0 + r - 32 W (bits below 0 do not exist).
@@ -796,28 +675,10 @@ SparseWs sparse_ws_layout(int index_heads, int64_t n) {
     return w;
 }
 
-int check_qkv(const void* q, const void* k, const void* v, int q_heads, int kv_heads, int64_t n, float scale, void* o) {
-    if (!q || !k || !v || !o) return VS_ERR_INVALID_ARG;
-    if (!vs::aligned16(q) || !vs::aligned16(k) || !vs::aligned16(v) || !vs::aligned16(o)) return VS_ERR_INVALID_ARG;
-    if (q_heads <= 0 || kv_heads <= 0 || n <= 0) return VS_ERR_INVALID_ARG;
-    if (!(scale > 0.f) || !isfinite(scale)) return VS_ERR_INVALID_ARG;
-    if (q_heads % kv_heads != 0) return VS_ERR_UNSUPPORTED;
-    if (n > VS_MAX_SEQ) return VS_ERR_UNSUPPORTED;
-    return VS_OK;
-}
-
-int heads_per_workgroup(int group, bool index_per_q) {
-    if (index_per_q) return 1;
-    if (group % 4 == 0) return 4;
-    if (group % 2 == 0) return 2;
-    return 1;
-}
-
-template <bool DENSE>
 int launch_attention(AttnParams& p, hipStream_t stream) {
     static bool attr_set = false;
     if (!attr_set) {
-        VS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&vs_attention_kernel<DENSE>),
+        VS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&vs_attention_kernel),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kSmemBytes)));
         attr_set = true;
     }
@@ -837,7 +698,7 @@ int launch_attention(AttnParams& p, hipStream_t stream) {
         }
         launch = blocks < cus ? blocks : cus;                // the LDS footprint allows one workgroup per compute unit
     }
-    hipLaunchKernelGGL(vs_attention_kernel<DENSE>, dim3(static_cast<unsigned>(launch)), dim3(kThreads), kSmemBytes, stream, p);
+    hipLaunchKernelGGL(vs_attention_kernel, dim3(static_cast<unsigned>(launch)), dim3(kThreads), kSmemBytes, stream, p);
     VS_LAUNCH_CHECK();
     return VS_OK;
 }
@@ -926,29 +787,7 @@ int vs_sparse_prefill_tiled(const void* q, const void* k, const void* v, int q_h
     // one queue counter per KV head at bytes 128.. of the counter block (zeroed with the bitmaps above); more than 32
     // KV heads do not fit there: one workgroup per unit then
     p.work_counter = kv_heads <= 32 ? reinterpret_cast<unsigned int*>(base + w.counter_off + 128) : nullptr;
-    return launch_attention<false>(p, st);
-}
-
-int vs_dense_prefill(const void* q, const void* k, const void* v, int q_heads, int kv_heads, int64_t n, float scale,
-                     void* o_bf16, float* lse, void* stream) {
-    int rc = check_qkv(q, k, v, q_heads, kv_heads, n, scale, o_bf16);
-    if (rc != VS_OK) return rc;
-    AttnParams p{};
-    p.q = static_cast<const uint16_t*>(q);
-    p.k = static_cast<const uint16_t*>(k);
-    p.v = static_cast<const uint16_t*>(v);
-    p.o = static_cast<uint16_t*>(o_bf16);
-    p.lse = lse;
-    p.q_heads = q_heads;
-    p.kv_heads = kv_heads;
-    p.group = q_heads / kv_heads;
-    p.index_per_q = 0;
-    p.hc = heads_per_workgroup(p.group, false);
-    p.n = static_cast<int>(n);
-    p.scale = scale;
-    p.c = scale * 1.4426950408889634f;
-    p.tile_counter = nullptr;
-    return launch_attention<true>(p, static_cast<hipStream_t>(stream));
+    return launch_attention(p, st);
 }
 
 int vs_sparse_prefill_tiles(const void* ws, size_t ws_bytes, void* stream, int64_t* executed_tiles_host) {
