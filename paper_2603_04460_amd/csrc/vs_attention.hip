@@ -170,13 +170,15 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     const int st_ck = 4 * ((lane >> 2) & 3) + (((lane & 3) - st_rho) & 3);          // K chunk of this piece
     const int st_cv = 4 * ((((lane >> 2) & 3) - st_rho) & 3) + (lane & 3);          // V chunk of this piece
     // buf: which of the three stage buffers (0..2).  The loads complete in the background (vmcnt).
+    // The head's K / V base is wave-uniform; a thread adds a 32-bit byte offset: row * 256 + its chunk (n <= 2^20 rows).
+    const uint32_t st_bk = static_cast<uint32_t>(st_ck * 16), st_bv = static_cast<uint32_t>(st_cv * 16);
     auto load_stage = [&](const int (&rows)[2], int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             unsigned char* dst = kvbuf + (2 * buf + u) * kSlotBytes + wave * kGroupBytes;
-            const size_t off = static_cast<size_t>(rows[u]) * kD;
-            lds_load16(kbase + off + st_ck * 8, dst);
-            lds_load16(vbase + off + st_cv * 8, dst + kTileBytes);
+            const uint32_t off = static_cast<uint32_t>(rows[u]) << 8;
+            lds_load16s(off + st_bk, kbase, dst);
+            lds_load16s(off + st_bv, vbase, dst + kTileBytes);
         }
     };
 
@@ -323,7 +325,8 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     // stage s+1 (complete since the last barrier) and refills the buffer of stage s-1 with stage s+2, whose global loads
     // were started at the top of the step.  One barrier per step.  The two tiles of a stage go through one softmax
     // (one row maximum, one rescale decision) and their matrix products are issued as independent chains.
-    auto run_phase = [&](int ntiles, auto gather_tag) __attribute__((always_inline)) {
+    // nfull: leading stages in which this wavefront's row block keeps every key of both tiles (no mask, nothing to skip)
+    auto run_phase = [&](int ntiles, auto gather_tag, int nfull) __attribute__((always_inline)) {
         constexpr bool GATHER = decltype(gather_tag)::value;
         if (ntiles == 0) return;
         const int nstages = (ntiles + 1) >> 1;
@@ -334,9 +337,11 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
                 // rows past the sequence and tiles past the list read row 0 instead: their scores are masked, so the
                 // loads need no predicate
                 int row = 0;
-                if (t < ntiles) {
-                    row = GATHER ? glist[32 * t + st_row] : 32 * list[t] + st_row;
-                    if (row >= n) row = 0;
+                if (GATHER) {
+                    // the list is padded with INT_MAX to a whole stage
+                    row = min(glist[32 * t + st_row], n - 1);
+                } else if (t < ntiles) {
+                    row = min(32 * list[t] + st_row, n - 1);
                 }
                 rows[u] = row;
             }
@@ -360,8 +365,15 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
         __builtin_amdgcn_s_waitcnt(0x0F70);                  // the barrier publishes only what has arrived
         __syncthreads();
         bf16x8 k0[8], k1[8], vf[8], p0[2], p1[2];
-        TileInfo a = info(0), b = info(1);
-        if (a.live) read_k(0, k0);
+        nfull = min(nfull, nstages);
+        TileInfo a{false, false, 0ull, 0ull, 0u, nullptr}, b = a;
+        if (nfull > 0) {
+            read_k(0, k0);
+        } else {
+            a = info(0);
+            b = info(1);
+            if (a.live) read_k(0, k0);
+        }
         auto pv = [&](const bf16x8 (&pk)[2]) __attribute__((always_inline)) {
 #pragma unroll
             for (int t = 0; t < 2; ++t)                      // the four d-blocks in turn: consecutive MFMAs are independent
@@ -370,7 +382,9 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
         };
         int buf = 0;                                         // buffer of stage st; st+1 is in buf+1, st+2 goes to buf+2 (mod 3)
         // one step
-        auto step = [&](int st) __attribute__((always_inline)) {
+        // FULL: both tiles are kept whole by this row block: no tile descriptions, no masks, no tests
+        auto step = [&](int st, auto full_tag) __attribute__((always_inline)) {
+            constexpr bool FULL = decltype(full_tag)::value;
             if (st > 0) {
                 __builtin_amdgcn_s_waitcnt(0x0F70);          // this wavefront's part of stage st+1 has arrived
                 __syncthreads();
@@ -378,56 +392,64 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
             const int buf1 = buf == 2 ? 0 : buf + 1, buf2 = buf1 == 2 ? 0 : buf1 + 1;
             // list / bitmap words of the next stage are requested before the staging loads: the memory counters retire
             // in order, so waiting for them does not wait for the (younger) staging loads
-            const TileInfo na = info(2 * st + 2), nb = info(2 * st + 3);
+            TileInfo na{false, false, 0ull, 0ull, 0u, nullptr}, nb = na;
+            if constexpr (!FULL) {
+                na = info(2 * st + 2);
+                nb = info(2 * st + 3);
+            }
             const bool more = st + 2 < nstages;
             if (more) {                                      // into the buffer of stage st-1, free since the barrier
                 stage_rows(st + 2, rows);
                 load_stage(rows, buf2);
             }
-            f32x16 s0, s1;
+            // scores of the two tiles: defined only where the tile is live (every later use is under the same test), so
+            // that no registers are cleared for tiles that are skipped
+            f32x16 s0, s1, zero;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) s0[e] = s1[e] = 0.f;
+            for (int e = 0; e < 16; ++e) zero[e] = 0.f;
             // one chain after the other; the second tile's fragments are requested before the first chain starts
-            if (b.live) read_k(2 * buf + 1, k1);
-            if (a.live) {
+            const bool alive = FULL || a.live, blive = FULL || b.live;
+            if (blive) read_k(2 * buf + 1, k1);
+            if (alive) {
                 ++tiles_done;
 #pragma unroll
-                for (int kk = 0; kk < 8; ++kk) s0 = mfma32(k0[kk], qf[kk], s0);
+                for (int kk = 0; kk < 8; ++kk) s0 = mfma32(k0[kk], qf[kk], kk == 0 ? zero : s0);
             }
-            if (b.live) {
+            if (blive) {
                 ++tiles_done;
 #pragma unroll
-                for (int kk = 0; kk < 8; ++kk) s1 = mfma32(k1[kk], qf[kk], s1);
+                for (int kk = 0; kk < 8; ++kk) s1 = mfma32(k1[kk], qf[kk], kk == 0 ? zero : s1);
             }
-            if (na.live) read_k(2 * buf1, k0);               // first tile of the next stage: in LDS since the last barrier
-            if (a.live || b.live) {
+            // first tile of the next stage: in LDS since the last barrier (past the last stage: a stale slot, unused)
+            if (FULL || na.live) read_k(2 * buf1, k0);
+            if (alive || blive) {
                 float mx = NEG_INF;
-                if (a.live) {
-                    apply_mask(s0, a, gather_tag);
+                if (alive) {
+                    if constexpr (!FULL) apply_mask(s0, a, gather_tag);
                     mx = tile_max(s0);
                 }
-                if (b.live) {
-                    apply_mask(s1, b, gather_tag);
+                if (blive) {
+                    if constexpr (!FULL) apply_mask(s1, b, gather_tag);
                     mx = fmaxf(mx, tile_max(s1));
                 }
                 const float m_new = fmaxf(m_run, half_swap_max(mx));
                 if (__ballot((m_new - m_run) * p.c > kRescaleThreshold)) rescale(m_new);   // false when both are -inf
                 const float mc = (m_run == NEG_INF) ? 0.f : m_run * p.c;
                 float lsum = 0.f;
-                if (a.live) {
+                if (alive) {
                     exp_part(s0, 0, 16, mc, lsum);
                     pack_p(s0, p0);
                 }
-                if (b.live) {
+                if (blive) {
                     exp_part(s1, 0, 16, mc, lsum);
                     pack_p(s1, p1);
                 }
                 l_run += lsum;
-                if (a.live) {
+                if (alive) {
                     read_v(2 * buf, vf);
                     pv(p0);
                 }
-                if (b.live) {
+                if (blive) {
                     read_v(2 * buf + 1, vf);
                     pv(p1);
                 }
@@ -436,10 +458,13 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
             b = nb;
             buf = buf1;
         };
-        for (int st = 0; st < nstages; st += 2) {
-            step(st);
-            if (st + 1 < nstages) step(st + 1);
+        int st = 0;
+        for (; st < nfull; ++st) step(st, std::true_type{});
+        if (st > 0 && st < nstages) {                        // the K fragments of tile 2 st were requested by the last full step
+            a = info(2 * st);
+            b = info(2 * st + 1);
         }
+        for (; st < nstages; ++st) step(st, std::false_type{});
         __syncthreads();                                     // the ring and the list are reused by the next phase
     };
 
@@ -585,12 +610,23 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
             }
             if (gcount < 0) gcount = gather_round();         // ends with a barrier
             else __syncthreads();
-            run_phase(count, std::false_type{});
+            run_phase(count, std::false_type{}, 0);
         }
         // 3. vertical part: causal columns outside the marked blocks, gathered row by row
         if (gcount < 0) gcount = gather_round();
+        // leading stages of the gather list whose 64 columns all lie at or before this row block's first row
+        auto full_stages = [&](int count) __attribute__((always_inline)) -> int {
+            if (!my_rows) return 0;
+            int lo = 0, hi = count;
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (__builtin_amdgcn_readfirstlane(glist[mid]) <= my_i0) lo = mid + 1;
+                else hi = mid;
+            }
+            return lo >> 6;
+        };
         while (true) {
-            run_phase((gcount + 31) >> 5, std::true_type{});
+            run_phase((gcount + 31) >> 5, std::true_type{}, full_stages(gcount));
             if (cursor >= ncand) break;
             gcount = gather_round();
         }

@@ -13,7 +13,8 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("hq,hk,n", [(4, 1, 200), (1, 1, 1000), (2, 1, 300), (8, 1, 257), (8, 2, 64), (3, 1, 130),
-                                     (4, 1, 1), (4, 1, 31), (4, 1, 33)])
+                                     (4, 1, 1), (4, 1, 31), (4, 1, 33), (4, 1, 63), (4, 1, 64), (4, 1, 65), (4, 1, 127),
+                                     (4, 1, 129), (2, 2, 191), (1, 1, 511), (6, 2, 320), (16, 2, 700)])
 def test_dense_small(hq, hk, n):
     (q, k, v), (qb, kb, vb) = make_qkv(100 + n, hq, hk, n)
     o, lse = run_dense(q, k, v)
