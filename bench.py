@@ -31,8 +31,8 @@ PEAK_BF16_TFLOPS = 2500.0           # MI355X dense bf16 MFMA
 FLOP_PER_TILE = 4 * 128 * 32 * 32   # QK^T and PV of a 32-row x 32-key tile at head_dim 128
 # HBM bytes per launch of the sparse attention kernel at the default workload (C4, n = 131072, tau = 0.9), from the
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/c4_128k_hbm_counters.txt:
-# 1988383.4 KiB fetched x 0.99998 (plain-copy calibration) + 1480334.3 KiB written.  Other workloads report null.
-MEASURED_TRAFFIC_BYTES = 3551926203
+# 1865626.9 KiB fetched x 0.99998 (plain-copy calibration) + 1283734.1 KiB written.  Other workloads report null.
+MEASURED_TRAFFIC_BYTES = 3224945664
 
 
 def log(*a):
@@ -303,7 +303,7 @@ def main():
                    "budget_fraction": pairs / causal_pairs, "tile_coverage": tiles / dense_tiles,
                    "tile_efficiency": pairs / (tiles * 1024.0)},
         "paper_context": "paper reports 4.95x (8.42x aggressive) over FlashAttention at 128k on unstated NVIDIA hardware",
-        "roofline": {"kernel": "vs_attention_kernel<sparse>", "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+        "roofline": {"kernel": "vs_attention_kernel", "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                      "traffic": MEASURED_TRAFFIC_BYTES if (args.config == 4 and n == 131072 and args.tau == 0.9) else None,
                      "flop_per_launch": exec_flop, "avg_launch_ms": t_att, "executed_tiles": tiles},
