@@ -73,7 +73,8 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     const float NEG_INF = -INFINITY;
 
     // ---- which unit of work: (query tile, KV head, chunk of the group's query heads) ----
-    // Persistent launch: one workgroup per compute unit takes units from counters in the workspace until none is left.  With one workgroup per unit the hardware dispatcher left a compute unit idle for ~20 us between two of
+    // Persistent launch: one workgroup per compute unit takes units from counters in the workspace until none is
+    // left.  With one workgroup per unit the hardware dispatcher left a compute unit idle for ~20 us between two of
     // these 160 KB / 512-thread workgroups (measured: 23 % of the kernel at 128k; a unit lasts only ~90 us).  There is
     // one queue of units per KV head.  A workgroup starts in the queue of head (its XCD number) % kv_heads, so an XCD's
     // L2 mostly sees one head's K / V, and moves on to the next queue when its own is empty, so that heads with a
@@ -632,29 +633,41 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
         }
     }
 
-    // ---- epilogue: O = O^T / l, bf16 store; lse = m * scale + ln(l) ----
+    // ---- epilogue: O = O^T / l in bf16; lse = m * scale + ln(l) ----
+    // A lane holds 8-byte pieces of one output row; stored directly they would be 64 scattered pieces per instruction.
+    // The row block goes through the wavefront's own 8.5 KB of the (now idle) ring instead: written as held, read back
+    // 16 bytes per lane, so that 16 lanes store one whole 256-byte row and an instruction stores four rows.
     {
         const float l_tot = half_swap_sum(l_run);
         const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-        const int row = my_i0 + qi;
-        if (row < n) {
-            uint16_t* dst = p.o + (static_cast<size_t>(my_head) * n + row) * kD;
+        constexpr int kPitch = 256 + 16;                     // row pitch in LDS: 16-byte aligned, spreads the rows over the banks
+        static_assert(32 * kPitch <= kTileBytes && kWaves * kTileBytes <= kSlots * kSlotBytes, "staging area of the epilogue");
+        unsigned char* const stage = kvbuf + wave * kTileBytes;
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < 4; ++db)
 #pragma unroll
-                for (int a = 0; a < 4; ++a) {
-                    const f32x2 x01 = {oacc[db][4 * a] * inv, oacc[db][4 * a + 1] * inv};
-                    const f32x2 x23 = {oacc[db][4 * a + 2] * inv, oacc[db][4 * a + 3] * inv};
-                    const bf16x2 y01 = __builtin_convertvector(x01, bf16x2);
-                    const bf16x2 y23 = __builtin_convertvector(x23, bf16x2);
-                    uint2 out;
-                    out.x = __builtin_bit_cast(uint32_t, y01);
-                    out.y = __builtin_bit_cast(uint32_t, y23);
-                    *reinterpret_cast<uint2*>(dst + 32 * db + 8 * a + 4 * hh) = out;
-                }
-            if (p.lse && hh == 0)
-                p.lse[static_cast<size_t>(my_head) * n + row] = l_tot > 0.f ? m_run * p.scale + __logf(l_tot) : NEG_INF;
+            for (int a = 0; a < 4; ++a) {
+                const f32x2 x01 = {oacc[db][4 * a] * inv, oacc[db][4 * a + 1] * inv};
+                const f32x2 x23 = {oacc[db][4 * a + 2] * inv, oacc[db][4 * a + 3] * inv};
+                const bf16x2 y01 = __builtin_convertvector(x01, bf16x2);
+                const bf16x2 y23 = __builtin_convertvector(x23, bf16x2);
+                uint2 out;
+                out.x = __builtin_bit_cast(uint32_t, y01);
+                out.y = __builtin_bit_cast(uint32_t, y23);
+                *reinterpret_cast<uint2*>(stage + qi * kPitch + 2 * (32 * db + 8 * a + 4 * hh)) = out;
+            }
+        // (only this wavefront touches its staging area: no barrier, the compiler orders the LDS accesses)
+        const int srow = lane >> 4, schunk = lane & 15;
+        uint16_t* const obase = p.o + (static_cast<size_t>(my_head) * n + my_i0) * kD;
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            const int r = 4 * it + srow;
+            const uint4 piece = *reinterpret_cast<const uint4*>(stage + r * kPitch + 16 * schunk);
+            if (my_i0 + r < n) *reinterpret_cast<uint4*>(obase + static_cast<size_t>(r) * kD + 8 * schunk) = piece;
         }
+        const int row = my_i0 + qi;
+        if (row < n && p.lse && hh == 0)
+            p.lse[static_cast<size_t>(my_head) * n + row] = l_tot > 0.f ? m_run * p.scale + __logf(l_tot) : NEG_INF;
     }
     if (p.tile_counter && lane == 0 && tiles_done) atomicAdd(p.tile_counter, static_cast<unsigned long long>(tiles_done));
     if (!p.work_counter) break;
