@@ -149,20 +149,6 @@ __global__ __launch_bounds__(kThreads) void vs_dense_kernel(const AttnParams p) 
         for (int kk = 0; kk < 8; ++kk)
             kf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(kt + ((kk & 1) ? k_off2 : k_off0) + 64 * (kk >> 1)));
     };
-    auto read_v = [&](int slot, bf16x8 (&vf)[8]) __attribute__((always_inline)) {
-        const unsigned char* va = kvbuf + slot * kSlotBytes;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const unsigned char* a0 = va + v_off[j >> 1] + 4 * (j & 1) * kGroupBytes;
-            const bf16x4t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr_t)(a0));
-            const bf16x4t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr_t)(a0 + 2 * kGroupBytes));
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                vf[j][e] = lo[e];
-                vf[j][4 + e] = hi[e];
-            }
-        }
-    };
 
     bf16x8 kf[2][8], vf[2][8], pb[2][2][2];
     f32x16 sc[2][2];
@@ -175,31 +161,6 @@ __global__ __launch_bounds__(kThreads) void vs_dense_kernel(const AttnParams p) 
         const uint64_t w = (dlt < -31 || !my_rows[rb] || t >= nblk) ? 0ull : (dlt >= 31 ? kAll63 : ((kAll63 << (31 - dlt)) & kAll63));
         mask_elements<0>(acc, lane_keep_bits(w, w, 0u, qi + 4 - 4 * hh, 4 - 4 * hh), __float_as_uint(NEG_INF));
     };
-    auto tile_max = [&](const f32x16& acc) __attribute__((always_inline)) -> float {
-        float mx = fmaxf(fmaxf(acc[0], acc[1]), acc[2]);
-#pragma unroll
-        for (int e = 3; e < 15; e += 2) mx = fmaxf(fmaxf(mx, acc[e]), acc[e + 1]);
-        return fmaxf(mx, acc[15]);
-    };
-    auto exp_part = [&](f32x16& acc, float mc, float& lsum) __attribute__((always_inline)) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            acc[e] = __builtin_amdgcn_exp2f(fmaf(acc[e], p.c, -mc));
-            lsum += acc[e];
-        }
-    };
-    auto pack_p = [&](const f32x16& acc, bf16x8 (&pk)[2]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int e = 0; e < 8; e += 2) {
-                const f32x2 two = {acc[8 * t + e], acc[8 * t + e + 1]};
-                const bf16x2 r = __builtin_convertvector(two, bf16x2);
-                pk[t][e] = r[0];
-                pk[t][e + 1] = r[1];
-            }
-    };
-
     // One slot, written out in issue order: pieces are separated by scheduling barriers, so the matrix instructions
     // and the vector work alternate as listed.  MR: the row block whose matrix products are issued; VR = 1 - MR: the
     // row block whose softmax runs.  sq: stage whose scores are computed (HAS_Q); sq - 1: stage whose P V is
