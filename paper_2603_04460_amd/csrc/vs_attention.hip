@@ -1,11 +1,13 @@
 // Causal vertical-slash sparse attention for gfx950.
 //
-// One workgroup (8 wavefronts, two per SIMD) owns a query tile of one KV head: 8 row blocks of 32
-// query rows, arranged as hc query heads of the KV group times 8/hc consecutive 32-row sub-blocks
-// (hc = 4 for the 4:1 GQA layers: a 64-row tile of all four heads).  K / V tiles are staged once in
-// LDS for all eight row blocks.  Each wavefront owns one row block and stays under 256 VGPRs so that
-// two wavefronts share a SIMD: while one runs its softmax on the vector ALU the other keeps the
-// matrix core busy.
+// One workgroup (4 wavefronts, one per SIMD) owns a query tile of one KV head: 4 row blocks of 32
+// query rows, arranged as hc query heads of the KV group times 4/hc consecutive 32-row sub-blocks
+// (hc = 4 for the 4:1 GQA layers: a 32-row tile of all four heads).  K / V tiles are staged once in
+// LDS for all four row blocks.  Each wavefront owns one row block.  A workgroup stays under 80 KB of
+// LDS and 256 registers per lane, so that TWO workgroups share a compute unit: per unit of work the
+// set-up (index merge, lists) is a chain of memory round trips and barriers during which a workgroup
+// issues little, and the other workgroup's tile loop runs meanwhile; in steady state the two
+// wavefronts of a SIMD (one per workgroup) overlap softmax and matrix instructions.
 //
 // Scores are computed transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: a lane then holds
 // 16 keys of ONE query, which makes the row maximum a 16-way in-lane reduction plus one
@@ -30,9 +32,10 @@
 //      is all ones skip the mask, row blocks whose window is empty skip the tile.
 //
 // Staging: K / V rows go from global memory straight into LDS (global_load_lds_dwordx4: no staging registers, no LDS
-// store instructions).  The loads of stage s+2 are issued at the top of step s into the buffer that stage s-1 has just
-// left; each wavefront waits for its own loads (vmcnt) before the barrier that opens step s+1, which publishes them.
-// Loads are never predicated: rows that do not exist read row 0, whose scores are masked.
+// store instructions).  Two stage buffers: the loads of stage s+1 are issued at the top of step s, after its barrier,
+// into the buffer that stage s-1 has just left; each wavefront waits for its own loads (vmcnt) before the barrier that
+// opens step s+1, which publishes them.  Loads are never predicated: rows that do not exist read another row, whose
+// scores are masked.
 #include <hip/hip_runtime.h>
 #include <limits.h>
 #include <math.h>
@@ -45,37 +48,52 @@
 
 namespace {
 
-constexpr int kThreads = 512;
+constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
-constexpr int kListCap = 2048;                 // block list: kListCap / nsub entries per round
-constexpr int kGatherCap = 4096;               // entries of the per-round gather list
-constexpr int kTbitWords = 1024;               // touched-block bits for up to 32768 key blocks (n <= 2^20)
-// ring | block list | column word per listed block | offset windows per (sub-block, listed block) | touched bits | scratch | gather list
-constexpr size_t kListOff = kSlots * kSlotBytes;
-constexpr size_t kListVwOff = kListOff + kListCap * 4;
-constexpr size_t kListWOff = kListVwOff + (kListCap / 2) * 4;
-constexpr size_t kTbitOff = kListWOff + kListCap * 8;
-constexpr size_t kScratchOff = kTbitOff + kTbitWords * 4;
-constexpr size_t kGatherOff = kScratchOff + 128;
-constexpr size_t kSmemBytes = kGatherOff + kGatherCap * 4;
-static_assert(kSmemBytes <= 160 * 1024, "LDS of one compute unit");
+constexpr int kRing = 4;                       // ring of two stages of two tiles
+constexpr int kListCap = 128;                  // block list: kListCap / nsub entries per pass
+constexpr int kLdsBudget = 80 * 1024;          // per workgroup: two of them share the 160 KB of a compute unit
+// LDS: ring | block list | column word per listed block | offset windows per (sub-block, listed block) | scratch |
+// touched-block bits | gather list.  The touched-block bits need one bit per 32-key block of the sequence; the kernel
+// exists in two sizes so that the usual lengths keep a long gather list (entries per pass):
+//   LONG = false: n <= 131072 (128 words of bits), 2304 gather entries;  LONG = true: n <= 2^20 (1024 words), 1472.
+template <bool LONG>
+struct Lds {
+    static constexpr int kTbitWords = LONG ? 1024 : 128;
+    static constexpr int kGatherCap = LONG ? 1472 : 2304;
+    static constexpr size_t kListOff = kRing * kSlotBytes;
+    static constexpr size_t kListVwOff = kListOff + kListCap * 4;
+    static constexpr size_t kListWOff = kListVwOff + kListCap * 4;
+    static constexpr size_t kScratchOff = kListWOff + kListCap * 8;
+    static constexpr size_t kTbitOff = kScratchOff + 128;
+    static constexpr size_t kGatherOff = kTbitOff + kTbitWords * 4;
+    static constexpr size_t kBytes = kGatherOff + kGatherCap * 4;
+    static_assert(kBytes <= kLdsBudget, "two workgroups per compute unit");
+    static_assert(kGatherCap % 64 == 0 && kGatherCap >= 4 * kThreads, "whole stages; one batch of candidates must fit");
+};
+constexpr int kShortSeq = 131072;
 
-__global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams p) {
+// (the second launch bound caps the registers at 256 per lane, i.e. two wavefronts per SIMD: without it the compiler
+// takes accumulation registers for its spills and only one workgroup fits a compute unit)
+template <bool LONG>
+__global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnParams p) {
+    using L = Lds<LONG>;
+    constexpr int kGatherCap = L::kGatherCap;
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char* const kvbuf = smem;
-    int* const list = reinterpret_cast<int*>(smem + kListOff);
-    uint32_t* const list_vw = reinterpret_cast<uint32_t*>(smem + kListVwOff);
-    uint64_t* const list_w = reinterpret_cast<uint64_t*>(smem + kListWOff);
-    uint32_t* const tbits = reinterpret_cast<uint32_t*>(smem + kTbitOff);
-    int* const wtot = reinterpret_cast<int*>(smem + kScratchOff);
-    int* const glist = reinterpret_cast<int*>(smem + kGatherOff);
+    int* const list = reinterpret_cast<int*>(smem + L::kListOff);
+    uint32_t* const list_vw = reinterpret_cast<uint32_t*>(smem + L::kListVwOff);
+    uint64_t* const list_w = reinterpret_cast<uint64_t*>(smem + L::kListWOff);
+    uint32_t* const tbits = reinterpret_cast<uint32_t*>(smem + L::kTbitOff);
+    int* const wtot = reinterpret_cast<int*>(smem + L::kScratchOff);
+    int* const glist = reinterpret_cast<int*>(smem + L::kGatherOff);
 
     const float NEG_INF = -INFINITY;
 
     // ---- which unit of work: (query tile, KV head, chunk of the group's query heads) ----
-    // Persistent launch: one workgroup per compute unit takes units from counters in the workspace until none is
-    // left.  With one workgroup per unit the hardware dispatcher left a compute unit idle for ~20 us between two of
-    // these 160 KB / 512-thread workgroups (measured: 23 % of the kernel at 128k; a unit lasts only ~90 us).  There is
+    // Persistent launch: two workgroups per compute unit take units from counters in the workspace until none is
+    // left.  With one workgroup per unit the hardware dispatcher left a compute unit idle for ~20 us between two
+    // large workgroups (measured with 160 KB / 512 threads: 23 % of the kernel at 128k).  There is
     // one queue of units per KV head.  A workgroup starts in the queue of head (its XCD number) % kv_heads, so an XCD's
     // L2 mostly sees one head's K / V, and moves on to the next queue when its own is empty, so that heads with a
     // larger budget do not become the critical path.  Every wavefront leaves the loop at the same point.  (Without
@@ -122,7 +140,7 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
     const int hchunks = p.group / p.hc;
     const int hchunk = rest % hchunks;
     const int tile = p.tiles - 1 - rest / hchunks;          // longest tiles first
-    const int BQ = 256 / p.hc;
+    const int BQ = 32 * kWaves / p.hc;
     const int nsub = BQ >> 5;
     const int i0 = tile * BQ;
     const int n = p.n;
@@ -161,26 +179,28 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
         for (int e = 0; e < 16; ++e) oacc[db][e] = 0.f;
     unsigned int tiles_done = 0;
 
-    // ---- staging: a stage is two 32-key tiles; thread moves 16-byte chunk (tid & 15) of row (tid >> 4) of K and V of each ----
-    const int st_row = tid >> 4, st_chunk = tid & 15;
-    // thread (wavefront w, lane L) fills piece L of group w of a tile: row 4w + L/16 (= st_row); which 16-byte chunk of the
-    // row that piece holds follows from the rotations above
+    // ---- staging: a stage is two 32-key tiles; a thread moves one 16-byte chunk of rows st_row and st_row + 16 of K and V of each ----
+    const int st_row = tid >> 4;
+    // thread (wavefront w, lane L) fills piece L of groups w and w + 4 of a tile: rows 4w + L/16 (= st_row) and 16 more;
+    // which 16-byte chunk of the row that piece holds follows from the rotations above
     typedef const __attribute__((address_space(1))) void* gptr_t;
     typedef __attribute__((address_space(3))) void* lptr_t;
     const int st_rho = (lane >> 4) & 3;
     const int st_ck = 4 * ((lane >> 2) & 3) + (((lane & 3) - st_rho) & 3);          // K chunk of this piece
     const int st_cv = 4 * ((((lane >> 2) & 3) - st_rho) & 3) + (lane & 3);          // V chunk of this piece
-    // buf: which of the three stage buffers (0..2).  The loads complete in the background (vmcnt).
+    // buf: which of the two stage buffers.  The loads complete in the background (vmcnt).
     // The head's K / V base is wave-uniform; a thread adds a 32-bit byte offset: row * 256 + its chunk (n <= 2^20 rows).
     const uint32_t st_bk = static_cast<uint32_t>(st_ck * 16), st_bv = static_cast<uint32_t>(st_cv * 16);
-    auto load_stage = [&](const int (&rows)[2], int buf) __attribute__((always_inline)) {
+    auto load_stage = [&](const int (&rows)[2][2], int buf) __attribute__((always_inline)) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            unsigned char* dst = kvbuf + (2 * buf + u) * kSlotBytes + wave * kGroupBytes;
-            const uint32_t off = static_cast<uint32_t>(rows[u]) << 8;
-            lds_load16s(off + st_bk, kbase, dst);
-            lds_load16s(off + st_bv, vbase, dst + kTileBytes);
-        }
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                unsigned char* dst = kvbuf + (2 * buf + u) * kSlotBytes + (wave + kWaves * h) * kGroupBytes;
+                const uint32_t off = static_cast<uint32_t>(rows[u][h]) << 8;
+                lds_load16s(off + st_bk, kbase, dst);
+                lds_load16s(off + st_bv, vbase, dst + kTileBytes);
+            }
     };
 
     // ---- pieces of one (row block, 32-key tile) unit ----
@@ -322,29 +342,29 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
 
     // ---- pipeline over the tiles of one phase ----
     // GATHER == false: tile t is key block list[t];  GATHER == true: tile t is glist[32 t .. 32 t + 31].
-    // A stage is two tiles (64 keys).  Three stages live in LDS: step s computes on stage s, prefetches K fragments of
-    // stage s+1 (complete since the last barrier) and refills the buffer of stage s-1 with stage s+2, whose global loads
-    // were started at the top of the step.  One barrier per step.  The two tiles of a stage go through one softmax
-    // (one row maximum, one rescale decision) and their matrix products are issued as independent chains.
+    // A stage is two tiles (64 keys).  Two stages live in LDS: step s computes on stage s and refills the buffer of
+    // stage s-1 with stage s+1, whose global loads are started at the top of the step.  One barrier per step.  The two
+    // tiles of a stage go through one softmax (one row maximum, one rescale decision) and their matrix products are
+    // issued as independent chains.
     // nfull: leading stages in which this wavefront's row block keeps every key of both tiles (no mask, nothing to skip)
     auto run_phase = [&](int ntiles, auto gather_tag, int nfull) __attribute__((always_inline)) {
         constexpr bool GATHER = decltype(gather_tag)::value;
         if (ntiles == 0) return;
         const int nstages = (ntiles + 1) >> 1;
-        auto stage_rows = [&](int st, int (&rows)[2]) __attribute__((always_inline)) {
+        auto stage_rows = [&](int st, int (&rows)[2][2]) __attribute__((always_inline)) {
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 const int t = 2 * st + u;
-                // rows past the sequence and tiles past the list read row 0 instead: their scores are masked, so the
-                // loads need no predicate
-                int row = 0;
-                if (GATHER) {
-                    // the list is padded with INT_MAX to a whole stage
-                    row = min(glist[32 * t + st_row], n - 1);
-                } else if (t < ntiles) {
-                    row = min(32 * list[t] + st_row, n - 1);
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    // rows past the sequence and tiles past the list read another row instead: their scores are masked,
+                    // so the loads need no predicate
+                    const int r = st_row + 16 * h;
+                    int row = 0;
+                    if (GATHER) row = min(glist[32 * t + r], n - 1);       // the list is padded with INT_MAX to a whole stage
+                    else if (t < ntiles) row = min(32 * list[t] + r, n - 1);
+                    rows[u][h] = row;
                 }
-                rows[u] = row;
             }
         };
         auto info = [&](int t) __attribute__((always_inline)) -> TileInfo {
@@ -355,25 +375,17 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
         // Every vector memory load issued so far (the Q fragments) is waited for here, once.  Left pending, the first
         // use of Q inside the loop would wait for "all loads", including the staging loads issued just before it.
         __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0), other counters untouched
-        int rows[2];
-#pragma unroll
-        for (int st = 0; st < 2; ++st) {
-            if (st < nstages) {
-                stage_rows(st, rows);
-                load_stage(rows, st);
-            }
-        }
+        int rows[2][2];
+        stage_rows(0, rows);
+        load_stage(rows, 0);
         __builtin_amdgcn_s_waitcnt(0x0F70);                  // the barrier publishes only what has arrived
         __syncthreads();
         bf16x8 k0[8], k1[8], vf[8], p0[2], p1[2];
         nfull = min(nfull, nstages);
         TileInfo a{false, false, 0ull, 0ull, 0u, nullptr}, b = a;
-        if (nfull > 0) {
-            read_k(0, k0);
-        } else {
+        if (nfull == 0) {
             a = info(0);
             b = info(1);
-            if (a.live) read_k(0, k0);
         }
         auto pv = [&](const bf16x8 (&pk)[2]) __attribute__((always_inline)) {
 #pragma unroll
@@ -381,16 +393,16 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
 #pragma unroll
                 for (int db = 0; db < 4; ++db) oacc[db] = mfma32(vf[2 * db + t], pk[t], oacc[db]);
         };
-        int buf = 0;                                         // buffer of stage st; st+1 is in buf+1, st+2 goes to buf+2 (mod 3)
+        int buf = 0;                                         // buffer of stage st; stage st+1 goes to the other one
         // one step
         // FULL: both tiles are kept whole by this row block: no tile descriptions, no masks, no tests
         auto step = [&](int st, auto full_tag) __attribute__((always_inline)) {
             constexpr bool FULL = decltype(full_tag)::value;
             if (st > 0) {
-                __builtin_amdgcn_s_waitcnt(0x0F70);          // this wavefront's part of stage st+1 has arrived
+                __builtin_amdgcn_s_waitcnt(0x0F70);          // this wavefront's part of stage st has arrived
                 __syncthreads();
             }
-            const int buf1 = buf == 2 ? 0 : buf + 1, buf2 = buf1 == 2 ? 0 : buf1 + 1;
+            const int buf1 = buf ^ 1;
             // list / bitmap words of the next stage are requested before the staging loads: the memory counters retire
             // in order, so waiting for them does not wait for the (younger) staging loads
             TileInfo na{false, false, 0ull, 0ull, 0u, nullptr}, nb = na;
@@ -398,10 +410,10 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
                 na = info(2 * st + 2);
                 nb = info(2 * st + 3);
             }
-            const bool more = st + 2 < nstages;
+            const bool more = st + 1 < nstages;
             if (more) {                                      // into the buffer of stage st-1, free since the barrier
-                stage_rows(st + 2, rows);
-                load_stage(rows, buf2);
+                stage_rows(st + 1, rows);
+                load_stage(rows, buf1);
             }
             // scores of the two tiles: defined only where the tile is live (every later use is under the same test), so
             // that no registers are cleared for tiles that are skipped
@@ -410,6 +422,7 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
             for (int e = 0; e < 16; ++e) zero[e] = 0.f;
             // one chain after the other; the second tile's fragments are requested before the first chain starts
             const bool alive = FULL || a.live, blive = FULL || b.live;
+            if (alive) read_k(2 * buf, k0);
             if (blive) read_k(2 * buf + 1, k1);
             if (alive) {
                 ++tiles_done;
@@ -421,8 +434,6 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
 #pragma unroll
                 for (int kk = 0; kk < 8; ++kk) s1 = mfma32(k1[kk], qf[kk], kk == 0 ? zero : s1);
             }
-            // first tile of the next stage: in LDS since the last barrier (past the last stage: a stale slot, unused)
-            if (FULL || na.live) read_k(2 * buf1, k0);
             if (alive || blive) {
                 float mx = NEG_INF;
                 if (alive) {
@@ -461,7 +472,7 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
         };
         int st = 0;
         for (; st < nfull; ++st) step(st, std::true_type{});
-        if (st > 0 && st < nstages) {                        // the K fragments of tile 2 st were requested by the last full step
+        if (st > 0 && st < nstages) {
             a = info(2 * st);
             b = info(2 * st + 1);
         }
@@ -555,17 +566,21 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
             tbits[W] = acc;
         }
         __syncthreads();
-        // 2. slash part: marked blocks in ascending order.  Thread t owns words 2t and 2t+1 of the marks; an exclusive
+        // 2. slash part: marked blocks in ascending order.  Thread t owns kWpt consecutive words of the marks; an exclusive
         //    scan of the popcounts gives every marked block its position, and blocks are listed in rounds of bcap
         //    positions.  Each listed block gets its column word and, per 32-row sub-block of the tile, its window of
         //    the offset bitmap: all bitmap reads of the tile happen here, in parallel, not inside the attention loop.
         int nmarked;
         int my_pos;                                          // position of this thread's first marked block
-        uint32_t my_bits[2];
+        constexpr int kWpt = (L::kTbitWords + kThreads - 1) / kThreads;   // words of the marks per thread
+        uint32_t my_bits[kWpt];
         {
-            my_bits[0] = 2 * tid < nwords ? tbits[2 * tid] : 0u;
-            my_bits[1] = 2 * tid + 1 < nwords ? tbits[2 * tid + 1] : 0u;
-            const int mine = __popc(my_bits[0]) + __popc(my_bits[1]);
+            int mine = 0;
+#pragma unroll
+            for (int u = 0; u < kWpt; ++u) {
+                my_bits[u] = kWpt * tid + u < nwords ? tbits[kWpt * tid + u] : 0u;
+                mine += __popc(my_bits[u]);
+            }
             int incl = mine;
 #pragma unroll
             for (int d = 1; d < 64; d <<= 1) {
@@ -591,12 +606,12 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
             const int count = min(bcap, nmarked - rbase);
             int pos = my_pos - rbase;
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
+            for (int u = 0; u < kWpt; ++u) {
                 uint32_t bits = my_bits[u];
                 while (bits) {
                     const int j = __builtin_ctz(bits);
                     bits &= bits - 1u;
-                    if (pos >= 0 && pos < count) list[pos] = 32 * (2 * tid + u) + j;
+                    if (pos >= 0 && pos < count) list[pos] = 32 * (kWpt * tid + u) + j;
                     ++pos;
                 }
             }
@@ -641,7 +656,7 @@ __global__ __launch_bounds__(kThreads) void vs_attention_kernel(const AttnParams
         const float l_tot = half_swap_sum(l_run);
         const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
         constexpr int kPitch = 256 + 16;                     // row pitch in LDS: 16-byte aligned, spreads the rows over the banks
-        static_assert(32 * kPitch <= kTileBytes && kWaves * kTileBytes <= kSlots * kSlotBytes, "staging area of the epilogue");
+        static_assert(32 * kPitch <= kTileBytes && kWaves * kTileBytes <= kRing * kSlotBytes, "staging area of the epilogue");
         unsigned char* const stage = kvbuf + wave * kTileBytes;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
@@ -724,14 +739,15 @@ SparseWs sparse_ws_layout(int index_heads, int64_t n) {
     return w;
 }
 
+template <bool LONG>
 int launch_attention(AttnParams& p, hipStream_t stream) {
     static bool attr_set = false;
     if (!attr_set) {
-        VS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&vs_attention_kernel),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kSmemBytes)));
+        VS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&vs_attention_kernel<LONG>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(Lds<LONG>::kBytes)));
         attr_set = true;
     }
-    const int BQ = 256 / p.hc;
+    const int BQ = 32 * kWaves / p.hc;
     p.tiles = (p.n + BQ - 1) / BQ;
     const long long blocks = static_cast<long long>(p.kv_heads) * (p.group / p.hc) * p.tiles;
     if (blocks > 0x7fffffffLL) return VS_ERR_UNSUPPORTED;
@@ -745,9 +761,9 @@ int launch_attention(AttnParams& p, hipStream_t stream) {
             VS_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
             if (cus <= 0) cus = 256;
         }
-        launch = blocks < cus ? blocks : cus;                // the LDS footprint allows one workgroup per compute unit
+        launch = blocks < 2 * cus ? blocks : 2 * cus;        // LDS and registers allow two workgroups per compute unit
     }
-    hipLaunchKernelGGL(vs_attention_kernel, dim3(static_cast<unsigned>(launch)), dim3(kThreads), kSmemBytes, stream, p);
+    hipLaunchKernelGGL(vs_attention_kernel<LONG>, dim3(static_cast<unsigned>(launch)), dim3(kThreads), Lds<LONG>::kBytes, stream, p);
     VS_LAUNCH_CHECK();
     return VS_OK;
 }
@@ -836,7 +852,7 @@ int vs_sparse_prefill_tiled(const void* q, const void* k, const void* v, int q_h
     // one queue counter per KV head at bytes 128.. of the counter block (zeroed with the bitmaps above); more than 32
     // KV heads do not fit there: one workgroup per unit then
     p.work_counter = kv_heads <= 32 ? reinterpret_cast<unsigned int*>(base + w.counter_off + 128) : nullptr;
-    return launch_attention(p, st);
+    return n <= kShortSeq ? launch_attention<false>(p, st) : launch_attention<true>(p, st);
 }
 
 int vs_sparse_prefill_tiles(const void* ws, size_t ws_bytes, void* stream, int64_t* executed_tiles_host) {
