@@ -31,8 +31,8 @@ PEAK_BF16_TFLOPS = 2500.0           # MI355X dense bf16 MFMA
 FLOP_PER_TILE = 4 * 128 * 32 * 32   # QK^T and PV of a 32-row x 32-key tile at head_dim 128
 # HBM bytes per launch of the sparse attention kernel at the default workload (C4, n = 131072, tau = 0.9), from the
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/c4_128k_hbm_counters.txt:
-# 1904400.3 KiB fetched x 0.99998 (plain-copy calibration) + 1348958.2 KiB written.  Other workloads report null.
-MEASURED_TRAFFIC_BYTES = 3331400101
+# 2001626.9 KiB fetched x 0.99998 (plain-copy calibration) + 1316964.3 KiB written.  Other workloads report null.
+MEASURED_TRAFFIC_BYTES = 3398196395
 
 
 def log(*a):
