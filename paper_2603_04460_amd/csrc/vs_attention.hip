@@ -215,7 +215,7 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
 #pragma unroll
     for (int sgr = 0; sgr < 4; ++sgr) v_off[sgr] = v_lane + 64 * ((sgr + v_rho) & 3);
     typedef __attribute__((address_space(3))) bf16x4t* lds_ptr_t;
-    // slot: which of the six tile slots (wave-uniform)
+    // slot: which of the four tile slots (wave-uniform)
     auto read_k = [&](int slot, bf16x8 (&kf)[8]) __attribute__((always_inline)) {
         const unsigned char* kt = kvbuf + slot * kSlotBytes;
 #pragma unroll
