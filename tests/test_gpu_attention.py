@@ -172,8 +172,8 @@ def test_sparse_edge_cases():
 
 
 def test_sparse_many_tiles_sampled_rows():
-    """n = 16384, 8 / 2 heads: several hundred tiles per row block, > 4096 gathered columns (two gather
-    rounds), checked on a declared row sample."""
+    """n = 16384, 8 / 2 heads: several hundred tiles per row block, more gathered columns than one gather list holds
+    (several gather rounds), checked on a declared row sample."""
     n, hq, hk = 16384, 8, 2
     rng = np.random.default_rng(5)
     (q, k, v), (qb, kb, vb) = make_qkv(55, hq, hk, n)
@@ -187,8 +187,8 @@ def test_sparse_many_tiles_sampled_rows():
 
 
 def test_sparse_several_gather_rounds():
-    """Two slash offsets and 9000 selected columns at n = 16384: late query tiles gather almost all of them, more than
-    one gather list holds (4096 entries), so the kernel runs several gather rounds per tile."""
+    """Two slash offsets and 9000 selected columns at n = 16384: late query tiles gather almost all of them, several
+    times what one gather list holds (at most 2304 entries), so the kernel runs several gather rounds per tile."""
     n, hq, hk = 16384, 4, 1
     rng = np.random.default_rng(17)
     (q, k, v), (qb, kb, vb) = make_qkv(57, hq, hk, n)
@@ -202,13 +202,29 @@ def test_sparse_several_gather_rounds():
 
 def test_sparse_several_block_rounds():
     """Every 16th offset selected at n = 36000: every 32-key block is crossed by a selected diagonal, so late query
-    tiles list more blocks (1125) than one block list holds (1024 for a 64-row tile of four heads)."""
+    tiles list many more blocks (1125) than one block list holds (128): several block rounds per tile."""
     n, hq, hk = 36000, 4, 1
     (q, k, v), (qb, kb, vb) = make_qkv(58, hq, hk, n)
     iv, cv = lists([[0, 5, 17000]])
     is_, cs = lists([list(range(0, n, 16))])
     o, lse, tiles = run_sparse(q, k, v, iv, cv, is_, cs)
     rows = synth.sample_rows(18, n, 32, 96, 32)
+    ref_o, ref_lse = oracle.sparse_attention(qb, kb, vb, iv, cv, is_, cs, rows=rows)
+    check_attention(o, lse, ref_o, ref_lse, rows=rows)
+
+
+def test_sparse_long_sequence_class():
+    """n = 140000 (> 131072): the kernel size with 1024 words of touched-block bits and the shorter gather list, with a
+    4:1 group, a few thousand columns (several gather rounds late in the sequence) and banded offsets."""
+    n, hq, hk = 140000, 4, 1
+    rng = np.random.default_rng(23)
+    (q, k, v), (qb, kb, vb) = make_qkv(59, hq, hk, n)
+    cols = np.unique(np.concatenate([np.arange(4), rng.choice(n, size=4000, replace=False)]))
+    offs = np.unique(np.concatenate([np.arange(48), np.arange(70000, 70090), rng.choice(n, size=20, replace=False)]))
+    iv, cv = lists([cols])
+    is_, cs = lists([offs])
+    o, lse, tiles = run_sparse(q, k, v, iv, cv, is_, cs)
+    rows = synth.sample_rows(19, n, 40, 40, 48)
     ref_o, ref_lse = oracle.sparse_attention(qb, kb, vb, iv, cv, is_, cs, rows=rows)
     check_attention(o, lse, ref_o, ref_lse, rows=rows)
 
