@@ -81,3 +81,49 @@ def check_attention(o, lse, ref_o, ref_lse, rows=None, atol=ATTN_ATOL):
         lerr = np.abs(gl[fin] - ref_lse[fin]).max() if fin.any() else 0.0
         assert lerr <= 2e-3, "max-abs lse error %.4g" % lerr
     return err
+
+
+def probe_values(n):
+    """V for the key-set probe, [n, 128] float32 of zeros and ones (exact in bf16): channel c < 20 holds bit c of the key
+    number, channel 20 + r holds 1 iff key number % 108 == r."""
+    j = np.arange(n, dtype=np.int64)
+    v = np.zeros((n, 128), dtype=np.float32)
+    for c in range(20):
+        v[:, c] = (j >> c) & 1
+    v[j, 20 + (j % 108)] = 1.0
+    return v
+
+
+def check_key_set(k, idx_v, cnt_v, idx_s, cnt_s, hq, rows, granularity=None):
+    """Decisive check of WHICH keys a sparse call kept.  With q = 0 every kept key has weight 1 / |S_i|, so
+    lse[i] = ln |S_i| and o[i, c] * |S_i| is the number of kept keys whose probe channel c is one.  The oracle's kept
+    count must be reproduced exactly (exp(lse) rounds to it) and every channel count exactly where it is below 200 (the
+    bf16 output then still resolves single keys) and within 2^-8 relative above.  A dropped, duplicated or substituted
+    key changes the count, a bit channel or two residue channels."""
+    import oracle
+    hk, n, _ = k.shape
+    q = torch.zeros((hq, n, 128), dtype=torch.bfloat16, device="cuda")
+    vp = probe_values(n)
+    v = torch.from_numpy(vp).to(torch.bfloat16).cuda().unsqueeze(0).expand(hk, n, 128).contiguous()
+    o, lse, _ = run_sparse(q, k, v, idx_v, cnt_v, idx_s, cnt_s, granularity=granularity)
+    vb = synth.to_bits(v)
+    rows = np.asarray(rows, dtype=np.int64)
+    # the oracle needs q only for the scores (all zero here): a zero matrix of the right shape, K as given
+    ref_o, ref_lse, live = oracle.sparse_attention(np.zeros((hq, n, 128), dtype=np.uint16), synth.to_bits(k), vb,
+                                                   idx_v, cnt_v, idx_s, cnt_s, rows=rows, return_live=True,
+                                                   granularity=granularity or 1)
+    got_lse = lse[:, rows].cpu().numpy().astype(np.float64)
+    got_o = bf16_to_f64(o[:, rows])
+    empty = live == 0
+    assert np.array_equal(np.isneginf(got_lse), empty)
+    cnt_gpu = np.rint(np.exp(np.where(empty, 0.0, got_lse)))
+    assert np.array_equal(np.where(empty, 0, cnt_gpu).astype(np.int64), live), "kept-key counts differ"
+    assert np.abs(np.where(empty, 0.0, got_lse - ref_lse)).max() <= 1e-5 * max(1.0, np.log(float(live.max())))
+    ref_cnt = np.rint(ref_o * live[..., None])                       # exact integers from the oracle
+    got_cnt = got_o * live[..., None]
+    small = ref_cnt < 200
+    assert np.array_equal(np.rint(got_cnt[small]), ref_cnt[small]), "kept key sets differ (channel counts)"
+    big = ~small
+    if big.any():
+        assert (np.abs(got_cnt[big] - ref_cnt[big]) <= ref_cnt[big] * 2.0 ** -8).all(), "kept key sets differ (large counts)"
+    return live

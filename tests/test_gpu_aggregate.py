@@ -73,6 +73,23 @@ def test_aggregate_per_query_head(hq, hk, n):
     assert np.abs(a_v.sum(axis=1) - 1).max() < 1e-4 and np.abs(a_s.sum(axis=1) - 1).max() < 1e-4
 
 
+def test_aggregate_8192_one_head_elementwise():
+    """n = 8192, one head: 32 resident-key workgroups, 128 streamed stages each, the 512-entry diagonal ring wraps 16
+    times and every flush window is compared, element by element, together with the recall of a mask."""
+    hq, hk, n = 1, 1, 8192
+    rng = np.random.default_rng(8192)
+    (q, k, v), (qb, kb, vb) = make_qkv(8192, hq, hk, n, local=True)
+    sv = [np.concatenate([[0, 1, 2, 3], rng.choice(np.arange(4, n), 200, replace=False)])]
+    ss = [np.concatenate([np.arange(64), np.arange(3000, 3040), rng.choice(np.arange(64, n), 30, replace=False)])]
+    iv, cv = lists(sv)
+    is_, cs = lists(ss)
+    a_v, a_s, rec = _run(q, k, hq, mask=(iv, cv, is_, cs))
+    ref_v, ref_s, ref_r = _oracle(qb, kb, 1, mask=(iv, cv, is_, cs))
+    _close(a_v, ref_v)
+    _close(a_s, ref_s)
+    assert np.abs(rec - ref_r).max() <= RECALL_ABS, (rec, ref_r)
+
+
 def test_aggregate_group_mean_and_given_lse():
     """out_heads = kv_heads gives the mean over the group's query heads; passing the normalisers of the dense attention
     call instead of recomputing them gives the same vectors."""

@@ -7,7 +7,7 @@ import torch
 import oracle
 import paper_2603_04460_amd as vs
 from paper_2603_04460_amd import synth
-from gpu_util import make_qkv, run_sparse, run_dense, lists, check_attention, bf16_to_f64
+from gpu_util import make_qkv, run_sparse, run_dense, lists, check_attention, check_key_set, bf16_to_f64
 
 pytestmark = pytest.mark.gpu
 
@@ -274,3 +274,58 @@ def test_tile_granular_slash_mode(hq, hk, n, nv, ns):
         vs.sparse_prefill(q, k, v, torch.from_numpy(iv).cuda(), torch.from_numpy(cv).cuda(), torch.from_numpy(is_).cuda(),
                           torch.from_numpy(cs).cuda(), o, None, ws, slash_granularity=16)
     assert e.value.code == -2
+
+
+def _long_case(name):
+    """The list recipes of the long-sequence tests above: (n, hq, hk, column sets, offset sets, row sample)."""
+    if name == "gather_rounds":
+        n = 16384
+        cols = [np.random.default_rng(17).choice(n, size=9000, replace=False)]
+        return n, 4, 1, cols, [[0, 1]], synth.sample_rows(17, n, 40, 72, 48)
+    if name == "block_rounds":
+        n = 36000
+        return n, 4, 1, [[0, 5, 17000]], [list(range(0, n, 16))], synth.sample_rows(18, n, 32, 96, 32)
+    if name == "long_class":
+        n = 140000
+        rng = np.random.default_rng(23)
+        cols = np.unique(np.concatenate([np.arange(4), rng.choice(n, size=4000, replace=False)]))
+        offs = np.unique(np.concatenate([np.arange(48), np.arange(70000, 70090), rng.choice(n, size=20, replace=False)]))
+        return n, 4, 1, [cols], [offs], synth.sample_rows(19, n, 40, 40, 48)
+    if name == "many_tiles":
+        n = 16384
+        sv, ss = _random_sets(np.random.default_rng(5), n, 2, 6000, 700)
+        return n, 8, 2, sv, ss, synth.sample_rows(5, n, 48, 48, 64)
+    raise KeyError(name)
+
+
+@pytest.mark.parametrize("name,gran", [("gather_rounds", None), ("block_rounds", None), ("long_class", None),
+                                       ("many_tiles", None), ("many_tiles", 32), ("long_class", 32)])
+def test_key_sets_long_sequences(name, gran):
+    """Exact kept-key sets (count, bit channels, residue channels) of the multi-round / long-sequence cases: the value
+    tests above average thousands of keys and cannot see a single wrong key."""
+    n, hq, hk, sv, ss, rows = _long_case(name)
+    k = synth.qkv(900 + n, hq, hk, n)[1].cuda()
+    iv, cv = lists(sv)
+    is_, cs = lists(ss)
+    live = check_key_set(k, iv, cv, is_, cs, hq, rows, granularity=gran)
+    assert live.max() > 1000
+
+
+def test_key_sets_small_random():
+    """The same probe on 24 small random cases (every head layout, per-query-head lists, both granularities), all rows."""
+    rng = np.random.default_rng(777)
+    layouts = [(1, 1), (2, 1), (4, 1), (4, 2), (8, 2), (8, 1), (4, 4)]
+    for case in range(24):
+        hq, hk = layouts[int(rng.integers(len(layouts)))]
+        n = int(rng.choice([1, 33, 64, 255, 257, 500, 1000, 1025, 1777, 2600]))
+        per_q = bool(rng.integers(2)) and hq != hk
+        ih = hq if per_q else hk
+        sv, ss = _random_sets(rng, n, ih, int(rng.integers(0, n // 3 + 1)), int(rng.integers(1, n // 6 + 2)), runs=bool(rng.integers(2)))
+        gran = 32 if rng.integers(3) == 0 else None
+        iv, cv = lists(sv)
+        is_, cs = lists(ss)
+        k = synth.qkv(7000 + case, hq, hk, n)[1].cuda()
+        try:
+            check_key_set(k, iv, cv, is_, cs, hq, np.arange(n), granularity=gran)
+        except AssertionError as e:
+            raise AssertionError("case %d: heads %d/%d n %d per_q %s g %s: %s" % (case, hq, hk, n, per_q, gran, e))

@@ -14,7 +14,7 @@ import oracle
 import paper_2603_04460_amd as vs
 from paper_2603_04460_amd import synth
 import bench
-from gpu_util import check_attention
+from gpu_util import check_attention, check_key_set
 
 pytestmark = pytest.mark.gpu
 
@@ -92,6 +92,7 @@ def test_config2_fixed_budget_32k():
                                                    rows=rows, return_live=True)
     check_attention(o, lse, ref_o, ref_lse, rows=rows)
     assert tiles * 1024 >= bench.live_pairs(iv, cv, is_, cs, n, hq // hk)
+    check_key_set(k, iv, cv, is_, cs, hq, rows)
     # the planted heavy hitters really dominate their rows: the selected set contains them when scores say so
     assert live.min() >= 1
 
@@ -114,6 +115,8 @@ def test_pipeline_configs(config, n, taus):
         assert fractions[0.85] <= fractions[0.9] <= fractions[0.95]
     rows = synth.sample_rows(config, n, 24, 24, 48)
     _check_attention(w, lists, rows)
+    # exact kept-key sets of the selected lists at full size (q = 0 probe), sampled rows of every query head
+    check_key_set(w.k, *lists, w.hq, rows)
 
 
 def test_dense_full_size_sampled_rows():

@@ -9,7 +9,7 @@ import torch
 import paper_2603_04460_amd as vs
 from paper_2603_04460_amd import synth
 from oracle import vs_oracle as oracle
-from gpu_util import make_qkv, lists, run_sparse, run_dense, check_attention
+from gpu_util import make_qkv, lists, run_sparse, run_dense, check_attention, check_key_set
 
 pytestmark = pytest.mark.gpu
 
@@ -36,6 +36,9 @@ def test_sparse_attention_max_n(qkv):
     ref_o, ref_lse = oracle.sparse_attention(qb, kb, vb, iv, cv, is_, cs, rows=rows)
     check_attention(o, lse, ref_o, ref_lse, rows=rows)
     assert tiles > 0
+    # which keys were kept, exactly (the values above average hundreds of keys)
+    check_key_set(k, iv, cv, is_, cs, 1, rows)
+    check_key_set(k, iv, cv, is_, cs, 1, rows, granularity=32)
 
 
 def test_dense_attention_max_n(qkv):

@@ -246,18 +246,36 @@ def test_vs_aggregate_and_recall():
 
 
 def _granular_mask(n, I_v, I_s, g):
-    """The tile-granular kept set written directly from its definition (numpy, no oracle code)."""
-    I_v, I_s = set(int(x) for x in I_v), set(int(x) for x in I_s)
+    """The tile-granular kept set from its range form (numpy, no oracle code): with b = g * floor(i / g) the first row of
+    the aligned block of i, offset o reaches the keys b - o .. b + g - 1 - o (rows past the end of the sequence reach
+    nothing); a selected column is kept as in the exact mask; then causality."""
     M = np.full((n, n), -np.inf)
     for i in range(n):
-        first = g * (i // g)
+        b = g * (i // g)
+        last_row = min(b + g, n) - 1
+        for o in I_s:
+            lo, hi = max(b - int(o), 0), min(last_row - int(o), i)
+            if lo <= hi:
+                M[i, lo:hi + 1] = 0.0
+        for c in I_v:
+            if int(c) <= i:
+                M[i, int(c)] = 0.0
+    return M
+
+
+def _window_mask(n, I_s, g, forward):
+    """Two MISREADINGS of "the block of row i", for contrast with the aligned blocks: a sliding window of the g rows
+    ending at i (forward = False) or starting at i (forward = True)."""
+    M = np.zeros((n, n), dtype=bool)
+    for i in range(n):
+        block = range(i, min(i + g, n)) if forward else range(max(i - g + 1, 0), i + 1)
         for j in range(i + 1):
-            if j in I_v or any((r - j) in I_s for r in range(first, min(first + g, n)) if r - j >= 0):
-                M[i, j] = 0.0
+            M[i, j] = any((r - j) in I_s for r in block)
     return M
 
 
 def test_tile_granular_hand_worked_example():
+    """n = 8, g = 4: the example whose tile-granular mask happens to be the dense causal mask."""
     n, I_v, I_s, rows = _read_gold("vs_mask_n8_g4.txt")
     d = 4
     q = np.zeros((1, n, d), dtype=np.uint16)
@@ -273,6 +291,35 @@ def test_tile_granular_hand_worked_example():
         np.testing.assert_allclose(out[0, i], vf[rows[i]].astype(np.float64).mean(axis=0), atol=1e-12)
     dense, _ = oracle.dense_attention(q, k, v)
     np.testing.assert_allclose(out, dense, atol=1e-13)
+
+
+def test_tile_granular_hand_worked_example_aligned_blocks():
+    """n = 12, g = 4, I_s = {0, 6}, no columns: the hand-listed rows separate aligned blocks (54 live pairs) from a
+    trailing window (60), a forward window (36), the exact mask (18) and the dense mask (78).  q = 0, so every output
+    row is the plain mean of V over the hand-listed keys."""
+    n, I_v, I_s, rows = _read_gold("vs_mask_n12_g4.txt")
+    assert (n, I_v, I_s) == (12, [], [0, 6])
+    d = 4
+    q = np.zeros((1, n, d), dtype=np.uint16)
+    k = rand_bits(np.random.default_rng(2), 1, n, d)
+    vf = (np.arange(n)[:, None] + np.array([0.0, 16.0, 32.0, 64.0])[None, :]).astype(np.float32)
+    v = f32_to_bf16_bits(vf)[None]
+    iv, cv = lists(I_v, cap=1)
+    is_, cs = lists(I_s)
+    out, lse, live = oracle.sparse_attention(q, k, v, iv, cv, is_, cs, return_live=True, granularity=4)
+    assert sum(len(r) for r in rows.values()) == 54 == int(live.sum())
+    for i in range(n):
+        assert live[0, i] == len(rows[i])
+        np.testing.assert_allclose(out[0, i], vf[rows[i]].astype(np.float64).mean(axis=0), atol=1e-12)
+        np.testing.assert_allclose(lse[0, i], np.log(len(rows[i])), atol=1e-12)
+    # the fixture agrees with the range form, and the competing readings really differ on this example
+    kept = np.isfinite(_granular_mask(n, I_v, I_s, 4))
+    assert all(sorted(np.flatnonzero(kept[i]).tolist()) == rows[i] for i in range(n))
+    assert int(_window_mask(n, set(I_s), 4, forward=False).sum()) == 60
+    assert int(_window_mask(n, set(I_s), 4, forward=True).sum()) == 36
+    assert int(np.isfinite(vs_mask(n, I_v, I_s)).sum()) == 18
+    exact, _, live1 = oracle.sparse_attention(q, k, v, iv, cv, is_, cs, return_live=True, granularity=1)
+    assert int(live1.sum()) == 18
 
 
 @pytest.mark.parametrize("n,g,seed", [(24, 4, 0), (40, 8, 1), (70, 32, 2), (33, 32, 3), (16, 1, 4)])
