@@ -97,8 +97,9 @@ def probe_values(n):
 def check_key_set(k, idx_v, cnt_v, idx_s, cnt_s, hq, rows, granularity=None):
     """Decisive check of WHICH keys a sparse call kept.  With q = 0 every kept key has weight 1 / |S_i|, so
     lse[i] = ln |S_i| and o[i, c] * |S_i| is the number of kept keys whose probe channel c is one.  The oracle's kept
-    count must be reproduced exactly (exp(lse) rounds to it) and every channel count exactly where it is below 200 (the
-    bf16 output then still resolves single keys) and within 2^-8 relative above.  A dropped, duplicated or substituted
+    count must be reproduced exactly (exp(lse) rounds to it) and every channel count exactly where it is below 100 (the
+    bf16 output, 8 significant bits, then still resolves single keys: half an ulp is at most count * 2^-8 < 0.5) and
+    within half an ulp, 2^-8 relative, above.  A dropped, duplicated or substituted
     key changes the count, a bit channel or two residue channels."""
     import oracle
     hk, n, _ = k.shape
@@ -121,9 +122,13 @@ def check_key_set(k, idx_v, cnt_v, idx_s, cnt_s, hq, rows, granularity=None):
     assert np.abs(np.where(empty, 0.0, got_lse - ref_lse)).max() <= 1e-5 * max(1.0, np.log(float(live.max())))
     ref_cnt = np.rint(ref_o * live[..., None])                       # exact integers from the oracle
     got_cnt = got_o * live[..., None]
-    small = ref_cnt < 200
-    assert np.array_equal(np.rint(got_cnt[small]), ref_cnt[small]), "kept key sets differ (channel counts)"
+    small = ref_cnt < 100
+    bad = small & (np.rint(got_cnt) != ref_cnt)
+    if bad.any():
+        h, r, c = [int(x[0]) for x in np.nonzero(bad)]
+        raise AssertionError("kept key sets differ: head %d row %d channel %d: %.3f keys on the GPU, %d expected (|S| = %d); %d mismatches"
+                             % (h, rows[r], c, got_cnt[h, r, c], ref_cnt[h, r, c], live[h, r], int(bad.sum())))
     big = ~small
     if big.any():
-        assert (np.abs(got_cnt[big] - ref_cnt[big]) <= ref_cnt[big] * 2.0 ** -8).all(), "kept key sets differ (large counts)"
+        assert (np.abs(got_cnt[big] - ref_cnt[big]) <= ref_cnt[big] * 2.0 ** -8 + 1e-3).all(), "kept key sets differ (large counts)"
     return live
