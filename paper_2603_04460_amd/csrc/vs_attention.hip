@@ -15,21 +15,26 @@
 // second product O^T = V^T P^T.  V^T fragments come from LDS through the transposing read.
 //
 // Sparse path (Sec. "Fused attention kernel implementation" of the paper: indices read per query
-// tile, merged on the fly, keys fetched on demand).  The selected offsets and columns of a head are
-// expanded once into bitmaps.  Per query tile the workgroup
-//   1. marks the 32-key blocks that any selected diagonal crosses (they form the merged
-//      contiguous key ranges of the slash part),
-//   2. walks the sorted column list and keeps the columns that are causal for the tile and do NOT
-//      fall inside a marked block (those are covered by the block's own mask): the deduplicated
-//      gather list,
-//   3. streams marked blocks (coalesced rows) and gathered columns (row gathers) through LDS and
-//      runs online-softmax attention on them.  The exact element mask
-//          live(i, j) = j <= i and ( offset i-j selected  or  column j selected )
-//      is a 63-bit window of the offset bitmap per 32x32 tile plus a 32-bit column word, both
-//      wave-uniform (SGPRs).  Each lane shifts the window by its own query row, which leaves the
-//      keep-bits of its 16 accumulator elements in one register (four vector instructions per tile);
-//      an element then costs a bit-field extract and a bitwise select.  Interior tiles whose window
-//      is all ones skip the mask, row blocks whose window is empty skip the tile.
+// tile, merged on the fly, keys fetched on demand).  The slash part of the mask is shift-invariant: a
+// selected offset o crosses key block b for the 32-row block t exactly when it crosses block b + 1
+// for t + 1.  So one small kernel prepares, once per call and index head, the ascending list of
+// "block diagonals" delta = t - b that any selected offset crosses, with the 63-bit window of the
+// offset bitmap that belongs to each (it depends on delta only), plus the column bitmap.  Per query
+// tile the workgroup then
+//   1. lists the key blocks first_block(tile) - delta, delta <= first_block(tile): the merged
+//      contiguous key ranges of the slash part; each comes with its window and its column word,
+//   2. takes the leading entries of the sorted column list that are causal for the tile: the gather
+//      list.  A key that is both a selected column and reached by a selected offset belongs to the
+//      gather list only: the block tiles drop the listed columns (the deduplication),
+//   3. streams the listed blocks (coalesced rows) and the gathered columns (row gathers) through
+//      LDS and runs online-softmax attention on them.  The exact element mask of a block tile,
+//          live(i, j) = j <= i and offset i-j selected and column j not selected,
+//      is the 63-bit window and the 32-bit column word, both wave-uniform (SGPRs).  Each lane shifts
+//      the window by its own query row, which leaves the keep-bits of its 16 accumulator elements in
+//      one register; an element then costs a bit-field extract and a bitwise select.  Tiles whose
+//      window is all ones and whose column word is empty skip the mask, row blocks whose window is
+//      empty skip the tile.  A gathered tile needs a mask (column <= row) only in the one or two
+//      stages that straddle the row block's first row.
 //
 // Staging: K / V rows go from global memory straight into LDS (global_load_lds_dwordx4: no staging registers, no LDS
 // store instructions).  Two stage buffers: the loads of stage s+1 are issued at the top of step s, after its barrier,
@@ -41,6 +46,7 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "vs_attn_device.h"
@@ -54,39 +60,27 @@ constexpr int kRing = 4;                       // ring of two stages of two tile
 constexpr int kListCap = 128;                  // block list: kListCap / nsub entries per pass
 constexpr int kLdsBudget = 80 * 1024;          // per workgroup: two of them share the 160 KB of a compute unit
 // LDS: ring | block list | column word per listed block | offset windows per (sub-block, listed block) | scratch |
-// touched-block bits | gather list.  The touched-block bits need one bit per 32-key block of the sequence; the kernel
-// exists in two sizes so that the usual lengths keep a long gather list (entries per pass):
-//   LONG = false: n <= 131072 (128 words of bits), 2304 gather entries;  LONG = true: n <= 2^20 (1024 words), 1472.
-template <bool LONG>
-struct Lds {
-    static constexpr int kTbitWords = LONG ? 1024 : 128;
-    static constexpr int kGatherCap = LONG ? 1472 : 2304;
-    static constexpr size_t kListOff = kRing * kSlotBytes;
-    static constexpr size_t kListVwOff = kListOff + kListCap * 4;
-    static constexpr size_t kListWOff = kListVwOff + kListCap * 4;
-    static constexpr size_t kScratchOff = kListWOff + kListCap * 8;
-    static constexpr size_t kTbitOff = kScratchOff + 128;
-    static constexpr size_t kGatherOff = kTbitOff + kTbitWords * 4;
-    static constexpr size_t kBytes = kGatherOff + kGatherCap * 4;
-    static_assert(kBytes <= kLdsBudget, "two workgroups per compute unit");
-    static_assert(kGatherCap % 64 == 0 && kGatherCap >= 4 * kThreads, "whole stages; one batch of candidates must fit");
-};
-constexpr int kShortSeq = 131072;
+// gather list (entries per pass)
+constexpr int kGatherCap = 2496;
+constexpr size_t kListOff = kRing * kSlotBytes;
+constexpr size_t kListVwOff = kListOff + kListCap * 4;
+constexpr size_t kListWOff = kListVwOff + kListCap * 4;
+constexpr size_t kScratchOff = kListWOff + kListCap * 8;
+constexpr size_t kGatherOff = kScratchOff + 128;
+constexpr size_t kLdsBytes = kGatherOff + kGatherCap * 4;
+static_assert(kLdsBytes <= kLdsBudget, "two workgroups per compute unit");
+static_assert(kGatherCap % 64 == 0, "whole stages");
 
 // (the second launch bound caps the registers at 256 per lane, i.e. two wavefronts per SIMD: without it the compiler
 // takes accumulation registers for its spills and only one workgroup fits a compute unit)
-template <bool LONG>
 __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnParams p) {
-    using L = Lds<LONG>;
-    constexpr int kGatherCap = L::kGatherCap;
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char* const kvbuf = smem;
-    int* const list = reinterpret_cast<int*>(smem + L::kListOff);
-    uint32_t* const list_vw = reinterpret_cast<uint32_t*>(smem + L::kListVwOff);
-    uint64_t* const list_w = reinterpret_cast<uint64_t*>(smem + L::kListWOff);
-    uint32_t* const tbits = reinterpret_cast<uint32_t*>(smem + L::kTbitOff);
-    int* const wtot = reinterpret_cast<int*>(smem + L::kScratchOff);
-    int* const glist = reinterpret_cast<int*>(smem + L::kGatherOff);
+    int* const list = reinterpret_cast<int*>(smem + kListOff);
+    uint32_t* const list_vw = reinterpret_cast<uint32_t*>(smem + kListVwOff);
+    uint64_t* const list_w = reinterpret_cast<uint64_t*>(smem + kListWOff);
+    int* const wtot = reinterpret_cast<int*>(smem + kScratchOff);
+    int* const glist = reinterpret_cast<int*>(smem + kGatherOff);
 
     const float NEG_INF = -INFINITY;
 
@@ -151,9 +145,7 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
     const int my_i0 = i0 + 32 * (wave / p.hc);
     const bool my_rows = my_i0 < n;
     const int ih = p.index_per_q ? my_head : g;
-    const uint32_t* __restrict__ sbit = p.sbit + static_cast<size_t>(ih) * p.sw;
     const uint32_t* __restrict__ vbit = p.vbit + static_cast<size_t>(ih) * p.vw;
-    const uint32_t* __restrict__ t32 = p.t32 + static_cast<size_t>(ih) * p.tw;
 
     const uint16_t* __restrict__ kbase = p.k + static_cast<size_t>(g) * n * kD;
     const uint16_t* __restrict__ vbase = p.v + static_cast<size_t>(g) * n * kD;
@@ -277,25 +269,24 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
     struct TileInfo {
         bool live, need;
         uint64_t w, cz;          // contiguous tile: selected offsets / causal offsets window
-        uint32_t vw;             // contiguous tile: selected columns of the block
+        uint32_t fw, xw;         // contiguous tile: keys kept for every causal row / keys dropped (listed columns)
         const int* cols;         // gathered tile: its 32 column numbers in LDS
     };
     const int bcap = kListCap / nsub;                        // listed blocks per round
     const int my_sub = wave / p.hc;
     // t: position in the block list
     auto block_info = [&](int t) __attribute__((always_inline)) -> TileInfo {
-        TileInfo ti{false, false, 0ull, 0ull, 0u, nullptr};
+        TileInfo ti{false, false, 0ull, 0ull, 0u, 0u, nullptr};
         const int b = __builtin_amdgcn_readfirstlane(list[t]);
         const int dlt = my_i0 - 32 * b;                      // offset of (row 0, key 0) of the 32x32 tile
         if (dlt < -31 || !my_rows) return ti;                // every key lies after every row / padding rows
         ti.cz = dlt >= 31 ? kAll63 : ((kAll63 << (31 - dlt)) & kAll63);   // offsets >= 0
         // selected offsets dlt-31 .. dlt+31 at bits 0..62 and the block's column word, both prepared with the list
         ti.w = uniform64(list_w[my_sub * bcap + t]);
-        ti.vw = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(list_vw[t]));
+        ti.xw = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(list_vw[t]));
         if (p.gran == 32) {
             // Tile-granular slash: key kj is kept for every causal row of this 32-row block if ANY of its rows reaches it
-            // through a selected offset, i.e. if the window has a bit in [31 - kj, 62 - kj].  That is exactly how a
-            // selected column behaves inside the tile, so the keys join the column word and the offset window is dropped.
+            // through a selected offset, i.e. if the window has a bit in [31 - kj, 62 - kj].
             // x bit s = OR of window bits s .. s+len-1, len = rows of this block that exist (32 except at the end of
             // the sequence): doubling up to the largest power of two pw <= len, then two overlapping windows
             const int len = min(32, n - my_i0);
@@ -306,18 +297,18 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
                 pw *= 2;
             }
             x |= x >> (len - pw);
-            ti.vw |= __builtin_bitreverse32(static_cast<uint32_t>(x));
+            ti.fw = __builtin_bitreverse32(static_cast<uint32_t>(x)) & ~ti.xw;
             ti.w = 0ull;
-            ti.live = ti.vw != 0u && ti.cz != 0ull;
-            ti.need = !(ti.vw == 0xffffffffu && ti.cz == kAll63);
+            ti.live = ti.fw != 0u && ti.cz != 0ull;
+            ti.need = !(ti.fw == 0xffffffffu && ti.cz == kAll63);
             return ti;
         }
-        ti.live = (ti.w | (ti.vw ? ti.cz : 0ull)) != 0ull;
-        ti.need = ti.w != kAll63;
+        ti.live = ti.w != 0ull;
+        ti.need = ti.w != kAll63 || ti.xw != 0u;
         return ti;
     };
     auto gather_info = [&](const int* cols) __attribute__((always_inline)) -> TileInfo {
-        TileInfo ti{false, false, 0ull, 0ull, 0u, cols};
+        TileInfo ti{false, false, 0ull, 0ull, 0u, 0u, cols};
         const int cmin = cols[0], cmax = cols[31];           // ascending, INT_MAX padding
         ti.live = my_rows && cmin <= my_i0 + 31;
         ti.need = cmax > my_i0;
@@ -336,7 +327,7 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
                 if (c4.w > row) acc[4 * a + 3] = NEG_INF;
             }
         } else {
-            mask_elements<0>(acc, lane_keep_bits(ti.w, ti.cz, ti.vw, qi + 4 - 4 * hh, 4 - 4 * hh), __float_as_uint(NEG_INF));
+            mask_elements<0>(acc, lane_keep_bits(ti.w, ti.cz, ti.fw, ti.xw, qi + 4 - 4 * hh, 4 - 4 * hh), __float_as_uint(NEG_INF));
         }
     };
 
@@ -368,7 +359,7 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
             }
         };
         auto info = [&](int t) __attribute__((always_inline)) -> TileInfo {
-            if (t >= ntiles) return TileInfo{false, false, 0ull, 0ull, 0u, nullptr};
+            if (t >= ntiles) return TileInfo{false, false, 0ull, 0ull, 0u, 0u, nullptr};
             if (GATHER) return gather_info(glist + 32 * t);
             return block_info(t);
         };
@@ -382,7 +373,7 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
         __syncthreads();
         bf16x8 k0[8], k1[8], vf[8], p0[2], p1[2];
         nfull = min(nfull, nstages);
-        TileInfo a{false, false, 0ull, 0ull, 0u, nullptr}, b = a;
+        TileInfo a{false, false, 0ull, 0ull, 0u, 0u, nullptr}, b = a;
         if (nfull == 0) {
             a = info(0);
             b = info(1);
@@ -405,7 +396,7 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
             const int buf1 = buf ^ 1;
             // list / bitmap words of the next stage are requested before the staging loads: the memory counters retire
             // in order, so waiting for them does not wait for the (younger) staging loads
-            TileInfo na{false, false, 0ull, 0ull, 0u, nullptr}, nb = na;
+            TileInfo na{false, false, 0ull, 0ull, 0u, 0u, nullptr}, nb = na;
             if constexpr (!FULL) {
                 na = info(2 * st + 2);
                 nb = info(2 * st + 3);
@@ -481,168 +472,53 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
     };
 
     // ---- phases ----
-    const int nblk = i_last / 32 + 1;                       // key blocks that hold causal keys for this tile
     {
-        // 1. blocks crossed by a selected diagonal for any 32-row sub-block of the tile, one 32-block word per thread:
-        //    block b = 32 W + j is crossed by sub-block r iff T32 bit (qb0 + r - b) is set, so the word is the
-        //    bit-reversed 32-bit window of T32 that ends at qb0 + r - 32 W (bits below 0 do not exist).
-        const int qb0 = i0 >> 5;
-        const int nwords = (nblk + 31) >> 5;
-        // Gather candidates: the listed columns <= i_last, whose number was prepared per 32-row block
-        // (column_count_kernel).  Thread t takes four consecutive entries per batch.  The first batch is requested
-        // here, unpredicated (entries past the count are dropped later), so that it travels together with the bitmap
-        // reads below instead of costing a round trip of its own after the slash part.
+        const int qb0 = i0 >> 5;                             // first 32-row block of the tile
         const int32_t* __restrict__ iv = p.idx_v + static_cast<size_t>(ih) * p.cap_v;
-        const int ncand = p.ncol32[static_cast<size_t>(ih) * p.nq32 + (i_last >> 5)];
-        int cand[4];
-        auto load_candidates = [&](int cursor) __attribute__((always_inline)) {
-#pragma unroll
-            for (int u = 0; u < 4; ++u) cand[u] = iv[min(cursor + 4 * tid + u, p.cap_v - 1)];
-        };
-        load_candidates(0);
-        bool cand_loaded = true;
-        int cursor = 0;
-        // One round of the gather list: batches of 4 * kThreads candidates are filtered (causal for the tile, not inside
-        // a marked block) and appended in order with ONE barrier per batch: position = kept entries of earlier
-        // wavefronts + of earlier lanes (four ballots) + of the lane's own earlier entries.  Wave totals alternate
-        // between two buffers so that a fast wavefront's next batch cannot overwrite totals still being read.
+        const int32_t* __restrict__ ncol = p.ncol32 + static_cast<size_t>(ih) * p.nq32;
+        const int32_t* __restrict__ dl = p.dlist + static_cast<size_t>(ih) * p.dcap;
+        const unsigned long long* __restrict__ wl = p.wlist + static_cast<size_t>(ih) * p.dcap * 4;
+        // slash part: the listed block diagonals <= qb0;  vertical part: the listed columns <= i_last (negative entries,
+        // a prefix of the ascending list, are skipped)
+        const int ndiag = p.ndiag[static_cast<size_t>(ih) * p.nq32 + qb0];
+        const int ncand = ncol[i_last >> 5];
+        int cursor = min(p.vfirst[ih], ncand);
+        // columns before this row block's first row: every row of the block keeps them (no mask in their stages)
+        const int nbefore = (my_rows && my_i0 >= 32) ? __builtin_amdgcn_readfirstlane(ncol[(my_i0 >> 5) - 1]) : 0;
+        // One round of the gather list: the next kGatherCap causal columns, copied as they are (ascending), padded with
+        // INT_MAX to a whole stage.  Returns the number of columns; sets first to the list position of the round's start.
+        int first = 0;
         auto gather_round = [&]() -> int {
-            int count = 0, par = 0;
-            while (cursor < ncand && count + 4 * kThreads <= kGatherCap) {
-                if (!cand_loaded) load_candidates(cursor);
-                cand_loaded = false;
-                bool flag[4];
-                int pre = 0, tot = 0;
-                const uint64_t lt = (1ull << lane) - 1ull;
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int c = cand[u];
-                    flag[u] = cursor + 4 * tid + u < ncand && c >= 0 && c <= i_last &&
-                              !((tbits[c >> 10] >> ((c >> 5) & 31)) & 1u);
-                    const uint64_t bal = __ballot(flag[u]);
-                    pre += __popcll(bal & lt);
-                    tot += __popcll(bal);
-                }
-                int* tot_buf = wtot + (1 + par) * kWaves;
-                if (lane == 0) tot_buf[wave] = tot;
-                __syncthreads();
-                int off = count + pre, all = 0;
-#pragma unroll
-                for (int i = 0; i < kWaves; ++i) {
-                    const int c = tot_buf[i];
-                    if (i < wave) off += c;
-                    all += c;
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    if (flag[u]) glist[off++] = cand[u];
-                count += all;
-                par ^= 1;
-                cursor += 4 * kThreads;
-            }
-            __syncthreads();
+            const int count = min(ncand - cursor, kGatherCap);
+            for (int t = tid; t < count; t += kThreads) glist[t] = iv[cursor + t];
             const int padded = (count + 63) & ~63;
             for (int t = count + tid; t < padded; t += kThreads) glist[t] = INT_MAX;
+            first = cursor;
+            cursor += count;
             __syncthreads();
             return count;
         };
-        for (int W = tid; W < nwords; W += kThreads) {
-            uint32_t acc = 0;
-            for (int r = 0; r < nsub; ++r) {
-                const int top = qb0 + r - 32 * W;            // diagonal index of block 32 W (bit 0 of the word)
-                if (top < 0) continue;
-                const int start = top - 31;
-                uint32_t win;
-                if (start >= 0) {
-                    const uint64_t two = (static_cast<uint64_t>(t32[(start >> 5) + 1]) << 32) | t32[start >> 5];
-                    win = static_cast<uint32_t>(two >> (start & 31));
-                } else {
-                    win = t32[0] << (-start);
-                }
-                acc |= __builtin_bitreverse32(win);
-            }
-            const int valid = nblk - 32 * W;                 // blocks of this word that exist
-            if (valid < 32) acc &= (1u << valid) - 1u;
-            tbits[W] = acc;
-        }
-        __syncthreads();
-        // 2. slash part: marked blocks in ascending order.  Thread t owns kWpt consecutive words of the marks; an exclusive
-        //    scan of the popcounts gives every marked block its position, and blocks are listed in rounds of bcap
-        //    positions.  Each listed block gets its column word and, per 32-row sub-block of the tile, its window of
-        //    the offset bitmap: all bitmap reads of the tile happen here, in parallel, not inside the attention loop.
-        int nmarked;
-        int my_pos;                                          // position of this thread's first marked block
-        constexpr int kWpt = (L::kTbitWords + kThreads - 1) / kThreads;   // words of the marks per thread
-        uint32_t my_bits[kWpt];
-        {
-            int mine = 0;
-#pragma unroll
-            for (int u = 0; u < kWpt; ++u) {
-                my_bits[u] = kWpt * tid + u < nwords ? tbits[kWpt * tid + u] : 0u;
-                mine += __popc(my_bits[u]);
-            }
-            int incl = mine;
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const int y = __shfl_up(incl, d);
-                if (lane >= d) incl += y;
-            }
-            if (lane == 63) wtot[wave] = incl;
-            __syncthreads();
-            int before = 0, total = 0;
-#pragma unroll
-            for (int i = 0; i < kWaves; ++i) {
-                const int c = wtot[i];
-                if (i < wave) before += c;
-                total += c;
-            }
-            my_pos = before + incl - mine;
-            nmarked = total;
-        }
-        // The first round of the gather list is built together with the first round of the block list, so that the
-        // bitmap reads of the one and the ballots of the other share their waits.
+        // 1. slash part: key blocks qb0 - delta in the order of the diagonal list (nearest block first), in rounds of bcap
+        //    blocks.  Each listed block gets its column word and, per 32-row sub-block of the tile, its offset window.
+        //    The first round of the gather list is copied with the first block round (one barrier for both).
         int gcount = -1;
-        for (int rbase = 0; rbase < nmarked; rbase += bcap) {
-            const int count = min(bcap, nmarked - rbase);
-            int pos = my_pos - rbase;
-#pragma unroll
-            for (int u = 0; u < kWpt; ++u) {
-                uint32_t bits = my_bits[u];
-                while (bits) {
-                    const int j = __builtin_ctz(bits);
-                    bits &= bits - 1u;
-                    if (pos >= 0 && pos < count) list[pos] = 32 * (kWpt * tid + u) + j;
-                    ++pos;
-                }
-            }
-            __syncthreads();
+        for (int rbase = 0; rbase < ndiag; rbase += bcap) {
+            const int count = min(bcap, ndiag - rbase);
             for (int e = tid; e < count; e += kThreads) {
-                const int b = list[e];
+                const int b = qb0 - dl[rbase + e];
+                list[e] = b;
                 list_vw[e] = vbit[b];
-                for (int r = 0; r < nsub; ++r) {
-                    const int dlt = i0 + 32 * r - 32 * b;
-                    list_w[r * bcap + e] = dlt < -31 ? 0ull : (window64(sbit, dlt + 33) & kAll63);
-                }
+                for (int r = 0; r < nsub; ++r) list_w[r * bcap + e] = wl[static_cast<size_t>(rbase + e) * 4 + r];
             }
             if (gcount < 0) gcount = gather_round();         // ends with a barrier
             else __syncthreads();
             run_phase(count, std::false_type{}, 0);
         }
-        // 3. vertical part: causal columns outside the marked blocks, gathered row by row
+        // 2. vertical part: the causal columns, gathered row by row
         if (gcount < 0) gcount = gather_round();
-        // leading stages of the gather list whose 64 columns all lie at or before this row block's first row
-        auto full_stages = [&](int count) __attribute__((always_inline)) -> int {
-            if (!my_rows) return 0;
-            int lo = 0, hi = count;
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                if (__builtin_amdgcn_readfirstlane(glist[mid]) <= my_i0) lo = mid + 1;
-                else hi = mid;
-            }
-            return lo >> 6;
-        };
         while (true) {
-            run_phase((gcount + 31) >> 5, std::true_type{}, full_stages(gcount));
+            const int nfull = max(0, min(nbefore - first, gcount)) >> 6;
+            run_phase((gcount + 31) >> 5, std::true_type{}, nfull);
             if (cursor >= ncand) break;
             gcount = gather_round();
         }
@@ -689,83 +565,247 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
     }
 }
 
-// t32 bit t = any selected offset in [32 t - 31, 32 t + 31]
-__global__ void block_diag_kernel(const uint32_t* sbit, int sw, uint32_t* t32, int tw, int nbits) {
-    const int ih = blockIdx.y;
-    const int t = blockIdx.x * blockDim.x + threadIdx.x;
-    bool any = false;
-    if (t < nbits) any = (window64(sbit + static_cast<size_t>(ih) * sw, 32 * t + 33) & kAll63) != 0ull;
-    const uint64_t bal = __ballot(any);
-    if ((threadIdx.x & 63) == 0 && t < tw * 32) {
-        uint32_t* dst = t32 + static_cast<size_t>(ih) * tw + (t >> 5);
-        dst[0] = static_cast<uint32_t>(bal);
-        if ((t >> 5) + 1 < tw) dst[1] = static_cast<uint32_t>(bal >> 32);
-    }
-}
+// ---- once per call: index lists -> bitmaps, block-diagonal list, per-block counts ----
+// One workgroup per index head.  The head's offset bitmap, then its column bitmap, is built in LDS (bit atomics stay on
+// chip) and written out with plain stores; everything derived from the offsets is read back from LDS.
+constexpr int kPrepThreads = 1024;
+struct PrepParams {
+    const int32_t* idx_v;
+    const int32_t* cnt_v;
+    int cap_v;
+    const int32_t* idx_s;
+    const int32_t* cnt_s;
+    int cap_s;
+    int n, nsub, nblk;
+    uint32_t* sbit;                 // per head: bit (o + 64) set iff offset o selected (64-bit zero guard in front, zero tail)
+    uint32_t* vbit;
+    int sw, vw;
+    int32_t* dlist;
+    unsigned long long* wlist;
+    int dcap;
+    int32_t* ndiag;
+    int32_t* ncol32;
+    int nq32;
+    int32_t* vfirst;
+    uint32_t* counters;             // 64 words at the head of the workspace, zeroed here
+};
 
-// ncol32[ih][q] = number of entries of the ascending column list that are <= 32 q + 31 (and < n)
-__global__ void column_count_kernel(const int32_t* idx, const int32_t* cnt, int cap, int n, int32_t* ncol32, int nq32) {
-    const int ih = blockIdx.y;
-    const int q = blockIdx.x * blockDim.x + threadIdx.x;
-    if (q >= nq32) return;
-    const int32_t* iv = idx + static_cast<size_t>(ih) * cap;
-    const int limit = min(32 * q + 31, n - 1);
-    int lo = 0, hi = min(cnt[ih], cap);
-    while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (iv[mid] <= limit) lo = mid + 1; else hi = mid;
+__global__ __launch_bounds__(kPrepThreads) void vs_prepare_kernel(const PrepParams p) {
+    extern __shared__ __align__(16) uint32_t bm[];           // max(sw, vw) words, then 32 words of scan scratch
+    const int ih = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t* const scan = bm + max(p.sw, p.vw);
+    if (ih == 0 && tid < 64) p.counters[tid] = 0u;
+    // offsets
+    for (int w = tid; w < p.sw; w += kPrepThreads) bm[w] = 0u;
+    __syncthreads();
+    const int cs = min(p.cnt_s[ih], p.cap_s);
+    for (int t = tid; t < cs; t += kPrepThreads) {
+        const int e = p.idx_s[static_cast<size_t>(ih) * p.cap_s + t];
+        if (e >= 0 && e < p.n) atomicOr(&bm[(e + 64) >> 5], 1u << ((e + 64) & 31));
     }
-    ncol32[static_cast<size_t>(ih) * nq32 + q] = lo;
+    __syncthreads();
+    uint32_t* const sbit = p.sbit + static_cast<size_t>(ih) * p.sw;
+    for (int w = tid; w < p.sw; w += kPrepThreads) sbit[w] = bm[w];
+    // Block diagonals.  Candidate c stands for delta = c - (nsub - 1); 32-row block t = delta + r of a query tile (r < nsub)
+    // crosses key block (tile's first block - delta) through the offsets 32 t - 31 .. 32 t + 31.  A thread owns a run
+    // of consecutive candidates; an exclusive scan of the per-thread counts gives the list positions.
+    const int nsub = p.nsub;
+    const int ncand = p.nblk + nsub - 1;
+    const int per = (ncand + kPrepThreads - 1) / kPrepThreads;
+    const int c0 = min(tid * per, ncand), c1 = min(c0 + per, ncand);
+    auto window = [&](int t) -> uint64_t {                   // offsets 32 t - 31 .. 32 t + 31 at bits 0..62
+        return t < 0 ? 0ull : (window64(bm, 32 * t + 33) & kAll63);
+    };
+    auto crossed = [&](int delta) -> bool {
+        uint64_t any = 0ull;
+        for (int r = 0; r < nsub; ++r) any |= window(delta + r);
+        return any != 0ull;
+    };
+    int mine = 0;
+    for (int c = c0; c < c1; ++c) mine += crossed(c - (nsub - 1)) ? 1 : 0;
+    int incl = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int y = __shfl_up(incl, d);
+        if (lane >= d) incl += y;
+    }
+    if (lane == 63) scan[wave] = incl;
+    __syncthreads();
+    int pos = incl - mine;
+    for (int i = 0; i < wave; ++i) pos += scan[i];
+    int32_t* const dl = p.dlist + static_cast<size_t>(ih) * p.dcap;
+    unsigned long long* const wl = p.wlist + static_cast<size_t>(ih) * p.dcap * 4;
+    int32_t* const nd = p.ndiag + static_cast<size_t>(ih) * p.nq32;
+    for (int c = c0; c < c1; ++c) {
+        const int delta = c - (nsub - 1);
+        if (crossed(delta)) {
+            dl[pos] = delta;
+            for (int r = 0; r < 4; ++r) wl[static_cast<size_t>(pos) * 4 + r] = r < nsub ? window(delta + r) : 0ull;
+            ++pos;
+        }
+        if (delta >= 0 && delta < p.nq32) nd[delta] = pos;  // listed diagonals <= delta
+    }
+    __syncthreads();
+    // columns
+    for (int w = tid; w < p.vw; w += kPrepThreads) bm[w] = 0u;
+    __syncthreads();
+    const int cv = min(p.cnt_v[ih], p.cap_v);
+    const int32_t* const iv = p.idx_v + static_cast<size_t>(ih) * p.cap_v;
+    for (int t = tid; t < cv; t += kPrepThreads) {
+        const int e = iv[t];
+        if (e >= 0 && e < p.n) atomicOr(&bm[e >> 5], 1u << (e & 31));
+    }
+    __syncthreads();
+    uint32_t* const vbit = p.vbit + static_cast<size_t>(ih) * p.vw;
+    for (int w = tid; w < p.vw; w += kPrepThreads) vbit[w] = bm[w];
+    // ncol32[q] = entries of the ascending list that are <= min(32 q + 31, n - 1);  vfirst = entries that are < 0
+    for (int q = tid; q <= p.nq32; q += kPrepThreads) {
+        const int limit = q < p.nq32 ? min(32 * q + 31, p.n - 1) : -1;
+        int lo = 0, hi = cv;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (iv[mid] <= limit) lo = mid + 1; else hi = mid;
+        }
+        if (q < p.nq32) p.ncol32[static_cast<size_t>(ih) * p.nq32 + q] = lo;
+        else p.vfirst[ih] = lo;
+    }
 }
 
 struct SparseWs {
-    size_t counter_off, sbit_off, vbit_off, t32_off, ncol_off, total;
-    int sw, vw, tw, nq32;
+    size_t counter_off, sbit_off, vbit_off, ncol_off, ndiag_off, vfirst_off, dlist_off, wlist_off, total;
+    int sw, vw, nq32, dcap;
 };
 
 SparseWs sparse_ws_layout(int index_heads, int64_t n) {
     SparseWs w;
     const int64_t nblk = (n + 31) / 32;
-    w.sw = static_cast<int>(vs::round_up(static_cast<size_t>(n + 64 + 160 + 31) / 32, 4));
+    const size_t ih = static_cast<size_t>(index_heads);
+    w.sw = static_cast<int>(vs::round_up(static_cast<size_t>(n + 64 + 320 + 31) / 32, 4));
     w.vw = static_cast<int>(vs::round_up(static_cast<size_t>(nblk + 4), 4));
-    w.tw = static_cast<int>(vs::round_up(static_cast<size_t>(nblk + 1 + 31) / 32 + 2, 4));
+    w.nq32 = static_cast<int>(nblk);
+    w.dcap = static_cast<int>(nblk + 4);
     w.counter_off = 0;
     w.sbit_off = 256;
-    w.vbit_off = w.sbit_off + static_cast<size_t>(index_heads) * w.sw * 4;
-    w.t32_off = w.vbit_off + static_cast<size_t>(index_heads) * w.vw * 4;
-    w.nq32 = static_cast<int>(nblk);
-    w.ncol_off = vs::round_up(w.t32_off + static_cast<size_t>(index_heads) * w.tw * 4, 256);
-    w.total = vs::round_up(w.ncol_off + static_cast<size_t>(index_heads) * w.nq32 * 4, 256);
+    w.vbit_off = w.sbit_off + ih * w.sw * 4;
+    w.ncol_off = vs::round_up(w.vbit_off + ih * w.vw * 4, 256);
+    w.ndiag_off = vs::round_up(w.ncol_off + ih * w.nq32 * 4, 256);
+    w.vfirst_off = vs::round_up(w.ndiag_off + ih * w.nq32 * 4, 256);
+    w.dlist_off = vs::round_up(w.vfirst_off + ih * 4, 256);
+    w.wlist_off = vs::round_up(w.dlist_off + ih * w.dcap * 4, 256);
+    w.total = vs::round_up(w.wlist_off + ih * w.dcap * 4 * 8, 256);
     return w;
 }
 
-template <bool LONG>
-int launch_attention(AttnParams& p, hipStream_t stream) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        VS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&vs_attention_kernel<LONG>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(Lds<LONG>::kBytes)));
-        attr_set = true;
+// Device-dependent launch facts, looked up once per device (and thread-safe).
+struct DeviceInfo {
+    int cus = 0;
+};
+int device_info(DeviceInfo& out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static DeviceInfo cache[kMaxDevices];
+    static bool attr_set[kMaxDevices] = {};
+    int dev = 0;
+    VS_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return VS_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!attr_set[dev]) {
+        VS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&vs_attention_kernel),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kLdsBytes)));
+        VS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&vs_prepare_kernel),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        int cus = 0;
+        VS_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        cache[dev].cus = cus > 0 ? cus : 256;
+        attr_set[dev] = true;
     }
+    out = cache[dev];
+    return VS_OK;
+}
+
+int launch_attention(AttnParams& p, hipStream_t stream) {
+    DeviceInfo info;
+    const int rc = device_info(info);
+    if (rc != VS_OK) return rc;
     const int BQ = 32 * kWaves / p.hc;
     p.tiles = (p.n + BQ - 1) / BQ;
     const long long blocks = static_cast<long long>(p.kv_heads) * (p.group / p.hc) * p.tiles;
     if (blocks > 0x7fffffffLL) return VS_ERR_UNSUPPORTED;
     p.work_total = static_cast<int>(blocks);
     long long launch = blocks;
-    if (p.work_counter) {
-        static int cus = 0;
-        if (cus == 0) {
-            int dev = 0;
-            VS_HIP(hipGetDevice(&dev));
-            VS_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-            if (cus <= 0) cus = 256;
-        }
-        launch = blocks < 2 * cus ? blocks : 2 * cus;        // LDS and registers allow two workgroups per compute unit
-    }
-    hipLaunchKernelGGL(vs_attention_kernel<LONG>, dim3(static_cast<unsigned>(launch)), dim3(kThreads), Lds<LONG>::kBytes, stream, p);
+    if (p.work_counter) launch = blocks < 2 * info.cus ? blocks : 2 * info.cus;   // two workgroups per compute unit
+    hipLaunchKernelGGL(vs_attention_kernel, dim3(static_cast<unsigned>(launch)), dim3(kThreads), kLdsBytes, stream, p);
     VS_LAUNCH_CHECK();
     return VS_OK;
+}
+
+// Runs the whole sparse call on a workspace that is known to be large enough.
+int sparse_prefill_on(unsigned char* base, const SparseWs& w, const void* q, const void* k, const void* v, int q_heads,
+                      int kv_heads, int64_t n, float scale, const int32_t* idx_v, const int32_t* cnt_v, int cap_v,
+                      const int32_t* idx_s, const int32_t* cnt_s, int cap_s, int index_heads, int slash_granularity,
+                      void* o_bf16, float* lse, hipStream_t st) {
+    AttnParams p{};
+    p.q = static_cast<const uint16_t*>(q);
+    p.k = static_cast<const uint16_t*>(k);
+    p.v = static_cast<const uint16_t*>(v);
+    p.o = static_cast<uint16_t*>(o_bf16);
+    p.lse = lse;
+    p.q_heads = q_heads;
+    p.kv_heads = kv_heads;
+    p.group = q_heads / kv_heads;
+    p.index_per_q = (index_heads == q_heads && q_heads != kv_heads) ? 1 : 0;
+    p.hc = heads_per_workgroup(p.group, p.index_per_q != 0);
+    p.gran = slash_granularity;
+    p.n = static_cast<int>(n);
+    p.scale = scale;
+    p.c = scale * 1.4426950408889634f;
+    p.idx_v = idx_v;
+    p.cnt_v = cnt_v;
+    p.cap_v = cap_v;
+    p.vbit = reinterpret_cast<const uint32_t*>(base + w.vbit_off);
+    p.vw = w.vw;
+    p.dlist = reinterpret_cast<const int32_t*>(base + w.dlist_off);
+    p.wlist = reinterpret_cast<const unsigned long long*>(base + w.wlist_off);
+    p.dcap = w.dcap;
+    p.ndiag = reinterpret_cast<const int32_t*>(base + w.ndiag_off);
+    p.ncol32 = reinterpret_cast<const int32_t*>(base + w.ncol_off);
+    p.nq32 = w.nq32;
+    p.vfirst = reinterpret_cast<const int32_t*>(base + w.vfirst_off);
+    p.tile_counter = reinterpret_cast<unsigned long long*>(base + w.counter_off);
+    // one queue counter per KV head at bytes 128.. of the counter block (zeroed by the preparation kernel); more than 32
+    // KV heads do not fit there: one workgroup per unit then
+    p.work_counter = kv_heads <= 32 ? reinterpret_cast<unsigned int*>(base + w.counter_off + 128) : nullptr;
+
+    DeviceInfo info;
+    int rc = device_info(info);
+    if (rc != VS_OK) return rc;
+    PrepParams pp{};
+    pp.idx_v = idx_v;
+    pp.cnt_v = cnt_v;
+    pp.cap_v = cap_v;
+    pp.idx_s = idx_s;
+    pp.cnt_s = cnt_s;
+    pp.cap_s = cap_s;
+    pp.n = p.n;
+    pp.nsub = kWaves / p.hc;
+    pp.nblk = w.nq32;
+    pp.sbit = reinterpret_cast<uint32_t*>(base + w.sbit_off);
+    pp.vbit = reinterpret_cast<uint32_t*>(base + w.vbit_off);
+    pp.sw = w.sw;
+    pp.vw = w.vw;
+    pp.dlist = reinterpret_cast<int32_t*>(base + w.dlist_off);
+    pp.wlist = reinterpret_cast<unsigned long long*>(base + w.wlist_off);
+    pp.dcap = w.dcap;
+    pp.ndiag = reinterpret_cast<int32_t*>(base + w.ndiag_off);
+    pp.ncol32 = reinterpret_cast<int32_t*>(base + w.ncol_off);
+    pp.nq32 = w.nq32;
+    pp.vfirst = reinterpret_cast<int32_t*>(base + w.vfirst_off);
+    pp.counters = reinterpret_cast<uint32_t*>(base + w.counter_off);
+    const size_t prep_lds = (static_cast<size_t>(w.sw > w.vw ? w.sw : w.vw) + 32) * 4;
+    if (prep_lds > 160 * 1024) return VS_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(vs_prepare_kernel, dim3(index_heads), dim3(kPrepThreads), prep_lds, st, pp);
+    VS_LAUNCH_CHECK();
+    return launch_attention(p, st);
 }
 
 }  // namespace
@@ -797,62 +837,9 @@ int vs_sparse_prefill_tiled(const void* q, const void* k, const void* v, int q_h
     const SparseWs w = sparse_ws_layout(index_heads, n);
     if (!ws || ws_bytes < w.total) return VS_ERR_WORKSPACE;
     if (!vs::aligned16(ws)) return VS_ERR_INVALID_ARG;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    unsigned char* base = static_cast<unsigned char*>(ws);
-    uint32_t* sbit = reinterpret_cast<uint32_t*>(base + w.sbit_off);
-    uint32_t* vbit = reinterpret_cast<uint32_t*>(base + w.vbit_off);
-    uint32_t* t32 = reinterpret_cast<uint32_t*>(base + w.t32_off);
-
-    const size_t words = w.total / 4;
-    hipLaunchKernelGGL(fill_zero_kernel, dim3(static_cast<unsigned>((words + 255) / 256)), dim3(256), 0, st,
-                       reinterpret_cast<uint32_t*>(base), words);
-    VS_LAUNCH_CHECK();
-    hipLaunchKernelGGL(set_bits_kernel, dim3((cap_s + 255) / 256, index_heads), dim3(256), 0, st, idx_s, cnt_s, cap_s,
-                       static_cast<int>(n), sbit, w.sw, 64);
-    VS_LAUNCH_CHECK();
-    hipLaunchKernelGGL(set_bits_kernel, dim3((cap_v + 255) / 256, index_heads), dim3(256), 0, st, idx_v, cnt_v, cap_v,
-                       static_cast<int>(n), vbit, w.vw, 0);
-    VS_LAUNCH_CHECK();
-    const int nbits = static_cast<int>((n + 31) / 32 + 1);
-    hipLaunchKernelGGL(block_diag_kernel, dim3((w.tw * 32 + 255) / 256, index_heads), dim3(256), 0, st, sbit, w.sw, t32, w.tw,
-                       nbits);
-    VS_LAUNCH_CHECK();
-    int32_t* ncol32 = reinterpret_cast<int32_t*>(base + w.ncol_off);
-    hipLaunchKernelGGL(column_count_kernel, dim3((w.nq32 + 255) / 256, index_heads), dim3(256), 0, st, idx_v, cnt_v, cap_v,
-                       static_cast<int>(n), ncol32, w.nq32);
-    VS_LAUNCH_CHECK();
-
-    AttnParams p{};
-    p.q = static_cast<const uint16_t*>(q);
-    p.k = static_cast<const uint16_t*>(k);
-    p.v = static_cast<const uint16_t*>(v);
-    p.o = static_cast<uint16_t*>(o_bf16);
-    p.lse = lse;
-    p.q_heads = q_heads;
-    p.kv_heads = kv_heads;
-    p.group = q_heads / kv_heads;
-    p.index_per_q = (index_heads == q_heads && q_heads != kv_heads) ? 1 : 0;
-    p.hc = heads_per_workgroup(p.group, p.index_per_q != 0);
-    p.gran = slash_granularity;
-    p.n = static_cast<int>(n);
-    p.scale = scale;
-    p.c = scale * 1.4426950408889634f;
-    p.idx_v = idx_v;
-    p.cnt_v = cnt_v;
-    p.cap_v = cap_v;
-    p.sbit = sbit;
-    p.vbit = vbit;
-    p.t32 = t32;
-    p.sw = w.sw;
-    p.vw = w.vw;
-    p.tw = w.tw;
-    p.ncol32 = ncol32;
-    p.nq32 = w.nq32;
-    p.tile_counter = reinterpret_cast<unsigned long long*>(base + w.counter_off);
-    // one queue counter per KV head at bytes 128.. of the counter block (zeroed with the bitmaps above); more than 32
-    // KV heads do not fit there: one workgroup per unit then
-    p.work_counter = kv_heads <= 32 ? reinterpret_cast<unsigned int*>(base + w.counter_off + 128) : nullptr;
-    return n <= kShortSeq ? launch_attention<false>(p, st) : launch_attention<true>(p, st);
+    return sparse_prefill_on(static_cast<unsigned char*>(ws), w, q, k, v, q_heads, kv_heads, n, scale, idx_v, cnt_v, cap_v,
+                             idx_s, cnt_s, cap_s, index_heads, slash_granularity, o_bf16, lse,
+                             static_cast<hipStream_t>(stream));
 }
 
 int vs_sparse_prefill_tiles(const void* ws, size_t ws_bytes, void* stream, int64_t* executed_tiles_host) {

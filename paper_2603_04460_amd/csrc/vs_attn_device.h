@@ -43,12 +43,18 @@ struct AttnParams {
     const int32_t* idx_v;
     const int32_t* cnt_v;
     int cap_v;
-    const uint32_t* sbit;           // per index head: bit (o + 64) set iff offset o selected
-    const uint32_t* vbit;           // per index head: bit j set iff column j selected
-    const uint32_t* t32;            // per index head: bit t set iff an offset in [32t-31, 32t+31] is selected
-    int sw, vw, tw;                 // words per head of the three bitmaps
-    const int32_t* ncol32;          // per index head and 32-row block q: number of listed columns <= 32 q + 31
-    int nq32;                       // entries per head of ncol32
+    // prepared once per call from the index lists (one set per index head):
+    const uint32_t* vbit;           // bit j set iff column j selected
+    int vw;                         // words per head of vbit
+    const int32_t* dlist;           // block diagonals, ascending: delta is listed iff a selected offset crosses key block
+                                    // (first row block of the tile - delta) for some 32-row block of a query tile
+    const unsigned long long* wlist;  // per listed diagonal and 32-row block r < 4: selected offsets 32 (delta + r) - 31 ..
+                                    // 32 (delta + r) + 31 at bits 0..62
+    int dcap;                       // entries per head of dlist (wlist: 4 dcap)
+    const int32_t* ndiag;           // per head and 32-row block q: number of listed diagonals <= q
+    const int32_t* ncol32;          // per head and 32-row block q: number of listed columns <= 32 q + 31
+    int nq32;                       // entries per head of ndiag and ncol32
+    const int32_t* vfirst;          // per head: position of the first non-negative entry of the column list
     unsigned long long* tile_counter;
     unsigned int* work_counter;     // persistent launch: next unit of every KV head's queue (zero at launch); null: one unit per workgroup
     int work_total;                 // units of work (query tiles x KV heads x head chunks)
@@ -77,11 +83,13 @@ __device__ __forceinline__ uint64_t uniform64(uint64_t x) {
 // Keep-bits of one lane of a 32x32 S^T tile.  Lane (q, h) holds, in accumulator element E = 4a + c, key kj = 8a + 4h + c
 // of query q; the result has that element's keep-bit at position 27 - 8a - c.
 // w: selected offsets dlt-31 .. dlt+31 at bits 0..62 (key kj of row q is offset bit 31 + q - kj); cz: the causal ones
-// among them; vw: selected columns of the block.  sh = q + 4 - 4h and ysh = 4 - 4h are per-lane constants.
-__device__ __forceinline__ uint32_t lane_keep_bits(uint64_t w, uint64_t cz, uint32_t vw, int sh, int ysh) {
+// among them; fw: keys kept for every causal row of the block; xw: keys dropped for every row.
+// sh = q + 4 - 4h and ysh = 4 - 4h are per-lane constants.
+__device__ __forceinline__ uint32_t lane_keep_bits(uint64_t w, uint64_t cz, uint32_t fw, uint32_t xw, int sh, int ysh) {
     const uint32_t x = static_cast<uint32_t>(w >> sh), cx = static_cast<uint32_t>(cz >> sh);
-    const uint32_t y = __builtin_bitreverse32(vw) >> ysh;   // bit 27 - 8a - c = column 8a + 4h + c
-    return x | (y & cx);
+    const uint32_t yf = __builtin_bitreverse32(fw) >> ysh;  // bit 27 - 8a - c = key 8a + 4h + c
+    const uint32_t yx = __builtin_bitreverse32(xw) >> ysh;
+    return (x | (yf & cx)) & ~yx;
 }
 
 // Four elements (one group a) at a time: the keep-bits spread over a word each (written out: from the C form the compiler

@@ -159,7 +159,7 @@ __global__ __launch_bounds__(kThreads) void vs_dense_kernel(const AttnParams p) 
         const int dlt = my_i0[rb] - 32 * t;
         if (dlt >= 31 && my_rows[rb]) return;
         const uint64_t w = (dlt < -31 || !my_rows[rb] || t >= nblk) ? 0ull : (dlt >= 31 ? kAll63 : ((kAll63 << (31 - dlt)) & kAll63));
-        mask_elements<0>(acc, lane_keep_bits(w, w, 0u, qi + 4 - 4 * hh, 4 - 4 * hh), __float_as_uint(NEG_INF));
+        mask_elements<0>(acc, lane_keep_bits(w, w, 0u, 0u, qi + 4 - 4 * hh, 4 - 4 * hh), __float_as_uint(NEG_INF));
     };
     // One slot, written out in issue order: pieces are separated by scheduling barriers, so the matrix instructions
     // and the vector work alternate as listed.  MR: the row block whose matrix products are issued; VR = 1 - MR: the
