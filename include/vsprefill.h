@@ -38,7 +38,8 @@ typedef enum {
     VS_ERR_UNSUPPORTED = -2, /* q_heads % kv_heads != 0, d_h not a multiple of 64 or > 1024, n > 2^20 ... */
     VS_ERR_WORKSPACE = -3,   /* ws_bytes smaller than the *_workspace() answer, or ws NULL when bytes are needed */
     VS_ERR_CAPACITY = -4,    /* forced entries alone exceed cap_v / cap_s, or caps <= 0 */
-    VS_ERR_HIP = -5          /* a HIP call failed; vs_last_hip_error() has the hipError_t */
+    VS_ERR_HIP = -5,         /* a HIP call failed; vs_last_hip_error() has the hipError_t */
+    VS_ERR_STATIC_LIMIT = -6 /* vs_sparse_prefill_static: the call needs more scratch than the library's fixed array holds */
 } vs_status;
 
 #define VS_HEAD_DIM 128
@@ -156,6 +157,23 @@ int vs_sparse_prefill_tiled(const void* q, const void* k, const void* v, int q_h
                             float scale, const int32_t* idx_v, const int32_t* cnt_v, int cap_v,
                             const int32_t* idx_s, const int32_t* cnt_s, int cap_s, int index_heads,
                             int slash_granularity, void* o_bf16, float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * vs_sparse_prefill for callers that cannot allocate or pass a workspace: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid allocation.  Same arguments, results and error behaviour as vs_sparse_prefill, but the
+ * scratch (bitmaps, diagonal lists, counters) lives in an array of VS_STATIC_SCRATCH_BYTES that the library holds on
+ * every GPU it runs on until the process ends; the call allocates nothing and frees nothing.
+ *   - A call whose vs_sparse_prefill_workspace() exceeds VS_STATIC_SCRATCH_BYTES returns VS_ERR_STATIC_LIMIT before
+ *     anything is launched (32 / 8 heads with one mask per KV head fit up to n = 262144; n = 2^20 fits with one or two
+ *     index heads).
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two threads)
+ *     race.  Calls that follow each other on one stream are safe; every call rewrites what it reads.
+ */
+#define VS_STATIC_SCRATCH_BYTES (4u << 20)
+int vs_sparse_prefill_static(const void* q, const void* k, const void* v, int q_heads, int kv_heads, int64_t n,
+                             float scale, const int32_t* idx_v, const int32_t* cnt_v, int cap_v,
+                             const int32_t* idx_s, const int32_t* cnt_s, int cap_s, int index_heads,
+                             void* o_bf16, float* lse, void* stream);
 
 /*
  * Dense causal attention on the same layout (Sec. "Attention Computation", Eqs. P, A, O, with

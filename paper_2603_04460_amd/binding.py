@@ -12,7 +12,8 @@ _lib = None
 
 EXPORTS = [
     "vs_rope_apply", "vs_index_score_workspace", "vs_index_score", "vs_select_budget_workspace", "vs_select_budget",
-    "vs_sparse_prefill_workspace", "vs_sparse_prefill", "vs_sparse_prefill_tiled", "vs_dense_prefill",
+    "vs_sparse_prefill_workspace", "vs_sparse_prefill", "vs_sparse_prefill_tiled", "vs_sparse_prefill_static",
+    "vs_dense_prefill",
     "vs_sparse_prefill_tiles", "vs_aggregate_workspace", "vs_aggregate",
     "vs_strerror", "vs_last_hip_error", "vs_version",
 ]
@@ -63,6 +64,7 @@ def _load():
     L.vs_sparse_prefill_workspace.restype = sz
     L.vs_sparse_prefill.argtypes = [vp, vp, vp, i32, i32, i64, f32, vp, vp, i32, vp, vp, i32, i32, vp, vp, vp, sz, vp]
     L.vs_sparse_prefill_tiled.argtypes = [vp, vp, vp, i32, i32, i64, f32, vp, vp, i32, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
+    L.vs_sparse_prefill_static.argtypes = [vp, vp, vp, i32, i32, i64, f32, vp, vp, i32, vp, vp, i32, i32, vp, vp, vp]
     L.vs_dense_prefill.argtypes = [vp, vp, vp, i32, i32, i64, f32, vp, vp, vp]
     L.vs_sparse_prefill_tiles.argtypes = [vp, sz, vp, ctypes.POINTER(ctypes.c_int64)]
     L.vs_aggregate_workspace.argtypes = [i32, i32, i32, i64]
@@ -211,6 +213,27 @@ def sparse_prefill(q, k, v, idx_v, cnt_v, idx_s, cnt_s, o, lse, ws, scale=None, 
                                                _ptr(cnt_v), idx_v.shape[1], _ptr(idx_s), _ptr(cnt_s), idx_s.shape[1],
                                                index_heads, int(slash_granularity), _ptr(o), _ptr(lse), _ptr(ws), ws_bytes,
                                                _stream(stream)), "vs_sparse_prefill_tiled")
+    return o
+
+
+def sparse_prefill_static(q, k, v, idx_v, cnt_v, idx_s, cnt_s, o, lse, scale=None, stream=None):
+    """vs_sparse_prefill without a workspace argument (the library's fixed per-GPU scratch array); allocates nothing."""
+    import torch
+    _dev(q, torch.bfloat16, "q"); _dev(k, torch.bfloat16, "k"); _dev(v, torch.bfloat16, "v"); _dev(o, torch.bfloat16, "o")
+    _dev(idx_v, torch.int32, "idx_v"); _dev(idx_s, torch.int32, "idx_s")
+    _dev(cnt_v, torch.int32, "cnt_v"); _dev(cnt_s, torch.int32, "cnt_s")
+    q_heads, n, d = q.shape
+    kv_heads = k.shape[0]
+    assert d == 128 and k.shape == (kv_heads, n, 128) and v.shape == k.shape and o.shape == q.shape
+    index_heads = idx_v.shape[0]
+    assert idx_s.shape[0] == index_heads and cnt_v.numel() == index_heads and cnt_s.numel() == index_heads
+    if lse is not None:
+        _dev(lse, torch.float32, "lse")
+        assert lse.shape == (q_heads, n)
+    scale = 128 ** -0.5 if scale is None else scale
+    _check(_load().vs_sparse_prefill_static(_ptr(q), _ptr(k), _ptr(v), q_heads, kv_heads, n, scale, _ptr(idx_v),
+                                            _ptr(cnt_v), idx_v.shape[1], _ptr(idx_s), _ptr(cnt_s), idx_s.shape[1],
+                                            index_heads, _ptr(o), _ptr(lse), _stream(stream)), "vs_sparse_prefill_static")
     return o
 
 

@@ -19,6 +19,7 @@ const char* vs_strerror(int status) {
         case VS_ERR_WORKSPACE: return "workspace missing or too small";
         case VS_ERR_CAPACITY: return "index list capacity too small for the forced entries";
         case VS_ERR_HIP: return "HIP runtime error (see vs_last_hip_error)";
+        case VS_ERR_STATIC_LIMIT: return "sizes exceed the library's fixed scratch array (use the workspace entry point)";
         default: return "unknown status";
     }
 }

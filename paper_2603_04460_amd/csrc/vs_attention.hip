@@ -696,9 +696,15 @@ SparseWs sparse_ws_layout(int index_heads, int64_t n) {
     return w;
 }
 
+// Scratch of the entry point that allocates nothing: one copy per GPU, held until the process ends.  In host code the
+// array's name is only a handle; its device address comes from hipGetSymbolAddress (device_info below).
+constexpr size_t kStaticScratchBytes = VS_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 // Device-dependent launch facts, looked up once per device (and thread-safe).
 struct DeviceInfo {
     int cus = 0;
+    unsigned char* scratch_ptr = nullptr;                    // this device's copy of `scratch`
 };
 int device_info(DeviceInfo& out) {
     constexpr int kMaxDevices = 64;
@@ -717,6 +723,10 @@ int device_info(DeviceInfo& out) {
         int cus = 0;
         VS_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
         cache[dev].cus = cus > 0 ? cus : 256;
+        void* sp = nullptr;
+        VS_HIP(hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch)));   // the current device's copy
+        if (!sp) return VS_ERR_HIP;
+        cache[dev].scratch_ptr = static_cast<unsigned char*>(sp);
         attr_set[dev] = true;
     }
     out = cache[dev];
@@ -840,6 +850,24 @@ int vs_sparse_prefill_tiled(const void* q, const void* k, const void* v, int q_h
     return sparse_prefill_on(static_cast<unsigned char*>(ws), w, q, k, v, q_heads, kv_heads, n, scale, idx_v, cnt_v, cap_v,
                              idx_s, cnt_s, cap_s, index_heads, slash_granularity, o_bf16, lse,
                              static_cast<hipStream_t>(stream));
+}
+
+int vs_sparse_prefill_static(const void* q, const void* k, const void* v, int q_heads, int kv_heads, int64_t n, float scale,
+                             const int32_t* idx_v, const int32_t* cnt_v, int cap_v, const int32_t* idx_s,
+                             const int32_t* cnt_s, int cap_s, int index_heads, void* o_bf16, float* lse, void* stream) {
+    int rc = check_qkv(q, k, v, q_heads, kv_heads, n, scale, o_bf16);
+    if (rc != VS_OK) return rc;
+    if (!idx_v || !cnt_v || !idx_s || !cnt_s || cap_v <= 0 || cap_s <= 0) return VS_ERR_INVALID_ARG;
+    if (index_heads != q_heads && index_heads != kv_heads) return VS_ERR_INVALID_ARG;
+    const SparseWs w = sparse_ws_layout(index_heads, n);
+    if (w.total > kStaticScratchBytes) return VS_ERR_STATIC_LIMIT;
+    DeviceInfo info;
+    rc = device_info(info);
+    if (rc != VS_OK) return rc;
+    // every structure the kernels read is rewritten by the preparation kernel of this call (counters included), so what
+    // the previous call left in the array does not matter
+    return sparse_prefill_on(info.scratch_ptr, w, q, k, v, q_heads, kv_heads, n, scale, idx_v, cnt_v, cap_v, idx_s, cnt_s,
+                             cap_s, index_heads, 1, o_bf16, lse, static_cast<hipStream_t>(stream));
 }
 
 int vs_sparse_prefill_tiles(const void* ws, size_t ws_bytes, void* stream, int64_t* executed_tiles_host) {
