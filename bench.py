@@ -25,7 +25,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 import paper_2603_04460_amd as vs  # noqa: E402
-from paper_2603_04460_amd import synth  # noqa: E402
+import synth  # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0           # MI355X dense bf16 MFMA
 FLOP_PER_TILE = 4 * 128 * 32 * 32   # QK^T and PV of a 32-row x 32-key tile at head_dim 128

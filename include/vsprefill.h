@@ -159,6 +159,37 @@ int vs_sparse_prefill_tiled(const void* q, const void* k, const void* v, int q_h
                             int slash_granularity, void* o_bf16, float* lse, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Chunked prefill (Sec. "Efficient VS Sparse Attention Inference": the same per-layer pipeline, applied to a block of
+ * new query positions against all keys so far).  vs_sparse_prefill_tiled for n_q query rows that are the positions
+ * pos0 .. pos0 + n_q - 1 of a sequence whose keys 0 .. n_kv - 1 are present:
+ *   q, o   [q_heads, n_q, 128];  k, v  [kv_heads, n_kv, 128];  lse [q_heads, n_q];  pos0 + n_q <= n_kv
+ * The mask speaks of absolute positions: the query at position i keeps key j iff j <= i and (j in I_v or i - j in I_s);
+ * lists hold columns and offsets in [0, n_kv).  Running the chunks of a sequence one after the other gives, row for
+ * row, the results of one call on the whole sequence (up to the order of summation).  pos0 may be any position for
+ * slash_granularity 1; granularity 32 groups positions in aligned blocks of 32 and needs pos0 % 32 == 0
+ * (VS_ERR_UNSUPPORTED otherwise).  Workspace: vs_sparse_prefill_workspace(q_heads, kv_heads, index_heads, n_kv).
+ *
+ * Batches: a batch of B sequences of equal length is B * q_heads query heads and B * kv_heads KV heads in the same
+ * layout ([B, heads, n, 128] contiguous), with one index list per (sequence, index head); every call of this library
+ * accepts that directly because head h always reads KV head h / (q_heads / kv_heads).
+ */
+int vs_sparse_prefill_chunk(const void* q, const void* k, const void* v, int q_heads, int kv_heads, int64_t n_q,
+                            int64_t n_kv, int64_t pos0, float scale, const int32_t* idx_v, const int32_t* cnt_v,
+                            int cap_v, const int32_t* idx_s, const int32_t* cnt_s, int cap_s, int index_heads,
+                            int slash_granularity, void* o_bf16, float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Debug check of index lists before they are given to vs_sparse_prefill / vs_aggregate (whose behaviour is undefined for
+ * lists that are not strictly ascending).  One report word per head, written on the device:
+ * 0 = usable, else a bit-or of the VS_LIST_* flags.  Out-of-range entries alone are legal input (they are ignored).
+ *   idx [heads, cap] int32, cnt [heads] int32, report [heads] int32 out (all device memory)
+ */
+#define VS_LIST_BAD_COUNT 1     /* cnt < 0 or cnt > cap */
+#define VS_LIST_OUT_OF_RANGE 2  /* an entry < 0 or >= n */
+#define VS_LIST_NOT_ASCENDING 4 /* an entry not larger than its predecessor (unsorted or duplicate) */
+int vs_validate_lists(const int32_t* idx, const int32_t* cnt, int cap, int heads, int64_t n, int32_t* report, void* stream);
+
+/*
  * vs_sparse_prefill for callers that cannot allocate or pass a workspace: code under HIP graph capture, tight serving
  * loops, harnesses that forbid allocation.  Same arguments, results and error behaviour as vs_sparse_prefill, but the
  * scratch (bitmaps, diagonal lists, counters) lives in an array of VS_STATIC_SCRATCH_BYTES that the library holds on
@@ -181,6 +212,11 @@ int vs_sparse_prefill_static(const void* q, const void* k, const void* v, int q_
  */
 int vs_dense_prefill(const void* q, const void* k, const void* v, int q_heads, int kv_heads, int64_t n,
                      float scale, void* o_bf16, float* lse, void* stream);
+
+/* The same for a chunk of n_q query rows at positions pos0 .. pos0 + n_q - 1 against n_kv keys (layouts as for
+ * vs_sparse_prefill_chunk). */
+int vs_dense_prefill_chunk(const void* q, const void* k, const void* v, int q_heads, int kv_heads, int64_t n_q,
+                           int64_t n_kv, int64_t pos0, float scale, void* o_bf16, float* lse, void* stream);
 
 size_t vs_aggregate_workspace(int q_heads, int kv_heads, int index_heads, int64_t n);
 

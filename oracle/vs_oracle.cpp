@@ -275,28 +275,34 @@ int vso_select(const float* scores, int heads, int64_t n, int mode, double tau, 
     return 0;
 }
 
-// Vertical-slash sparse attention.  q: [q_heads, n, d], k, v: [kv_heads, n, d] bf16.
+// Vertical-slash sparse attention.  q: [q_heads, n_q, d], k, v: [kv_heads, n, d] bf16.
+// Chunked prefill: the n_q query rows are the positions pos0 .. pos0 + n_q - 1 of a sequence whose keys 0 .. n - 1 are
+// present (pos0 + n_q <= n); n_q <= 0 means the whole sequence (n_q = n, pos0 = 0).  The mask speaks of absolute
+// positions: the query at position i keeps key j iff j <= i and (j in I_v or i - j in I_s).
 // Query head h reads KV head h / (q_heads / kv_heads); its index lists come from index head
 // h (index_heads == q_heads) or from its KV head (index_heads == kv_heads).
-// Kept set of row i: { j : 0 <= j <= i and ( j in I_v or i - j in I_s ) }, each key once.
-// granularity g > 1 selects the tile-granular slash variant: rows are grouped in blocks of g (row i belongs to
-// rows g*floor(i/g) .. g*floor(i/g)+g-1) and key j <= i is kept if it is a selected column or ANY row i' of the
-// block of i has i' - j in I_s.  g = 1 is the mask equation itself.
-// rows: optional list of row numbers (n_rows of them); NULL -> all n rows in order.
+// Kept set of position i: { j : 0 <= j <= i and ( j in I_v or i - j in I_s ) }, each key once.
+// granularity g > 1 selects the tile-granular slash variant: positions are grouped in aligned blocks of g (position i
+// belongs to g*floor(i/g) .. g*floor(i/g)+g-1, clipped to the positions that exist, i.e. < pos0 + n_q) and key j <= i is
+// kept if it is a selected column or ANY position i' of the block of i has i' - j in I_s.  g = 1 is the mask equation.
+// rows: optional list of LOCAL row numbers (n_rows of them, each in [0, n_q)); NULL -> all n_q rows in order.
 // out: [q_heads, n_rows, d] fp64; lse: [q_heads, n_rows] or NULL; live: [q_heads, n_rows] or NULL.
 int vso_sparse_attention(const uint16_t* q, const uint16_t* k, const uint16_t* v,
                          int q_heads, int kv_heads, int64_t n, int d, double scale,
                          const int32_t* idx_v, const int32_t* cnt_v, int64_t cap_v,
                          const int32_t* idx_s, const int32_t* cnt_s, int64_t cap_s, int index_heads,
                          int64_t granularity,
-                         const int64_t* rows, int64_t n_rows,
+                         const int64_t* rows, int64_t n_rows, int64_t n_q, int64_t pos0,
                          double* out, double* lse, int64_t* live, int threads) {
     if (!q || !k || !v || !idx_v || !cnt_v || !idx_s || !cnt_s || !out) return -1;
     if (q_heads <= 0 || kv_heads <= 0 || q_heads % kv_heads || n <= 0 || d <= 0) return -1;
     if (index_heads != q_heads && index_heads != kv_heads) return -1;
     if (granularity < 1) return -1;
-    if (!rows) n_rows = n;
+    if (n_q <= 0) { n_q = n; pos0 = 0; }
+    if (pos0 < 0 || pos0 + n_q > n) return -1;
+    if (!rows) n_rows = n_q;
     const int group = q_heads / kv_heads;
+    const int64_t n_pos = pos0 + n_q;                         // positions that exist
     // membership tables per index head
     std::vector<std::vector<char>> in_v(index_heads, std::vector<char>(n, 0)), in_s(index_heads, std::vector<char>(n, 0));
     for (int ih = 0; ih < index_heads; ++ih) {
@@ -311,22 +317,26 @@ int vso_sparse_attention(const uint16_t* q, const uint16_t* k, const uint16_t* v
             in_s[ih][o] = 1;
         }
     }
+    if (rows)
+        for (int64_t r = 0; r < n_rows; ++r)
+            if (rows[r] < 0 || rows[r] >= n_q) return -4;
     parallel_for(static_cast<int64_t>(q_heads) * n_rows, threads, [&](int64_t item) {
         int h = static_cast<int>(item / n_rows);
         int64_t r = item % n_rows;
-        int64_t i = rows ? rows[r] : r;
+        int64_t local = rows ? rows[r] : r;
+        int64_t i = pos0 + local;                             // absolute position of the query
         int g = h / group;
         int ih = index_heads == q_heads ? h : g;
         const std::vector<char>& cv = in_v[ih];
         const std::vector<char>& cs = in_s[ih];
         double l;
-        int64_t c = attention_row(q + (static_cast<int64_t>(h) * n + i) * d, k + static_cast<int64_t>(g) * n * d,
+        int64_t c = attention_row(q + (static_cast<int64_t>(h) * n_q + local) * d, k + static_cast<int64_t>(g) * n * d,
                                   v + static_cast<int64_t>(g) * n * d, i, d, scale,
                                   [&](int64_t j) {
                                       if (cv[j]) return true;
                                       const int64_t first = granularity * (i / granularity);
-                                      for (int64_t r = first; r < first + granularity && r < n; ++r)
-                                          if (r - j >= 0 && cs[r - j]) return true;
+                                      for (int64_t r2 = first; r2 < first + granularity && r2 < n_pos; ++r2)
+                                          if (r2 - j >= 0 && cs[r2 - j]) return true;
                                       return false;
                                   },
                                   out + item * d, &l);
@@ -336,21 +346,27 @@ int vso_sparse_attention(const uint16_t* q, const uint16_t* k, const uint16_t* v
     return 0;
 }
 
+// Dense causal attention; chunk arguments (n_q, pos0, local rows) as for vso_sparse_attention.
 int vso_dense_attention(const uint16_t* q, const uint16_t* k, const uint16_t* v,
                         int q_heads, int kv_heads, int64_t n, int d, double scale,
-                        const int64_t* rows, int64_t n_rows, double* out, double* lse, int threads) {
+                        const int64_t* rows, int64_t n_rows, int64_t n_q, int64_t pos0, double* out, double* lse, int threads) {
     if (!q || !k || !v || !out) return -1;
     if (q_heads <= 0 || kv_heads <= 0 || q_heads % kv_heads || n <= 0 || d <= 0) return -1;
-    if (!rows) n_rows = n;
+    if (n_q <= 0) { n_q = n; pos0 = 0; }
+    if (pos0 < 0 || pos0 + n_q > n) return -1;
+    if (!rows) n_rows = n_q;
+    if (rows)
+        for (int64_t r = 0; r < n_rows; ++r)
+            if (rows[r] < 0 || rows[r] >= n_q) return -4;
     const int group = q_heads / kv_heads;
     parallel_for(static_cast<int64_t>(q_heads) * n_rows, threads, [&](int64_t item) {
         int h = static_cast<int>(item / n_rows);
         int64_t r = item % n_rows;
-        int64_t i = rows ? rows[r] : r;
+        int64_t local = rows ? rows[r] : r;
         int g = h / group;
         double l;
-        attention_row(q + (static_cast<int64_t>(h) * n + i) * d, k + static_cast<int64_t>(g) * n * d,
-                      v + static_cast<int64_t>(g) * n * d, i, d, scale, [](int64_t) { return true; },
+        attention_row(q + (static_cast<int64_t>(h) * n_q + local) * d, k + static_cast<int64_t>(g) * n * d,
+                      v + static_cast<int64_t>(g) * n * d, pos0 + local, d, scale, [](int64_t) { return true; },
                       out + item * d, &l);
         if (lse) lse[item] = l;
     });

@@ -123,44 +123,47 @@ def _lists(idx, cnt):
 
 
 def sparse_attention(q, k, v, idx_v, cnt_v, idx_s, cnt_s, scale=None, rows=None, threads=0, return_live=False,
-                     granularity=1):
-    """q: [Hq, n, d], k, v: [Hkv, n, d] uint16.  idx_*: [index_heads, cap] int32 ascending, cnt_*: [index_heads].
-    granularity g > 1: tile-granular slash variant (a key is kept for a row if any row of its g-row block reaches it
-    through a selected offset).  Returns (out [Hq, n_rows, d] f64, lse [Hq, n_rows] f64[, live [Hq, n_rows] int64])."""
+                     granularity=1, pos0=0):
+    """q: [Hq, n_q, d], k, v: [Hkv, n, d] uint16.  idx_*: [index_heads, cap] int32 ascending, cnt_*: [index_heads].
+    The query rows are the positions pos0 .. pos0 + n_q - 1 (chunked prefill; pos0 + n_q <= n); `rows` are local row
+    numbers.  granularity g > 1: tile-granular slash variant (a key is kept for a position if any position of its aligned
+    g-block reaches it through a selected offset).
+    Returns (out [Hq, n_rows, d] f64, lse [Hq, n_rows] f64[, live [Hq, n_rows] int64])."""
     L = _load()
     q = _c(q, np.uint16); k = _c(k, np.uint16); v = _c(v, np.uint16)
-    hq, n, d = q.shape
-    hk = k.shape[0]
+    hq, n_q, d = q.shape
+    hk, n = k.shape[0], k.shape[1]
     idx_v, cnt_v = _lists(idx_v, cnt_v); idx_s, cnt_s = _lists(idx_s, cnt_s)
     ih = idx_v.shape[0]
     assert idx_s.shape[0] == ih
     scale = 1.0 / np.sqrt(d) if scale is None else scale
     rows_a = None if rows is None else _c(rows, np.int64)
-    nr = n if rows is None else rows_a.size
+    nr = n_q if rows is None else rows_a.size
     out = np.empty((hq, nr, d), dtype=np.float64); lse = np.empty((hq, nr), dtype=np.float64)
     live = np.empty((hq, nr), dtype=np.int64)
     rc = L.vso_sparse_attention(_p(q), _p(k), _p(v), ctypes.c_int(hq), ctypes.c_int(hk), ctypes.c_int64(n),
                                 ctypes.c_int(d), ctypes.c_double(scale),
                                 _p(idx_v), _p(cnt_v), ctypes.c_int64(idx_v.shape[1]),
                                 _p(idx_s), _p(cnt_s), ctypes.c_int64(idx_s.shape[1]), ctypes.c_int(ih),
-                                ctypes.c_int64(granularity), _p(rows_a), ctypes.c_int64(nr), _p(out), _p(lse), _p(live), ctypes.c_int(threads))
+                                ctypes.c_int64(granularity), _p(rows_a), ctypes.c_int64(nr), ctypes.c_int64(n_q),
+                                ctypes.c_int64(pos0), _p(out), _p(lse), _p(live), ctypes.c_int(threads))
     if rc != 0:
         raise ValueError("vso_sparse_attention rc=%d" % rc)
     return (out, lse, live) if return_live else (out, lse)
 
 
-def dense_attention(q, k, v, scale=None, rows=None, threads=0):
+def dense_attention(q, k, v, scale=None, rows=None, threads=0, pos0=0):
     L = _load()
     q = _c(q, np.uint16); k = _c(k, np.uint16); v = _c(v, np.uint16)
-    hq, n, d = q.shape
-    hk = k.shape[0]
+    hq, n_q, d = q.shape
+    hk, n = k.shape[0], k.shape[1]
     scale = 1.0 / np.sqrt(d) if scale is None else scale
     rows_a = None if rows is None else _c(rows, np.int64)
-    nr = n if rows is None else rows_a.size
+    nr = n_q if rows is None else rows_a.size
     out = np.empty((hq, nr, d), dtype=np.float64); lse = np.empty((hq, nr), dtype=np.float64)
     rc = L.vso_dense_attention(_p(q), _p(k), _p(v), ctypes.c_int(hq), ctypes.c_int(hk), ctypes.c_int64(n),
                                ctypes.c_int(d), ctypes.c_double(scale), _p(rows_a), ctypes.c_int64(nr),
-                               _p(out), _p(lse), ctypes.c_int(threads))
+                               ctypes.c_int64(n_q), ctypes.c_int64(pos0), _p(out), _p(lse), ctypes.c_int(threads))
     if rc != 0:
         raise ValueError("vso_dense_attention rc=%d" % rc)
     return out, lse

@@ -12,8 +12,8 @@ _lib = None
 
 EXPORTS = [
     "vs_rope_apply", "vs_index_score_workspace", "vs_index_score", "vs_select_budget_workspace", "vs_select_budget",
-    "vs_sparse_prefill_workspace", "vs_sparse_prefill", "vs_sparse_prefill_tiled", "vs_sparse_prefill_static",
-    "vs_dense_prefill",
+    "vs_sparse_prefill_workspace", "vs_sparse_prefill", "vs_sparse_prefill_tiled", "vs_sparse_prefill_chunk",
+    "vs_sparse_prefill_static", "vs_dense_prefill", "vs_dense_prefill_chunk", "vs_validate_lists",
     "vs_sparse_prefill_tiles", "vs_aggregate_workspace", "vs_aggregate",
     "vs_strerror", "vs_last_hip_error", "vs_version",
 ]
@@ -66,6 +66,10 @@ def _load():
     L.vs_sparse_prefill_tiled.argtypes = [vp, vp, vp, i32, i32, i64, f32, vp, vp, i32, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
     L.vs_sparse_prefill_static.argtypes = [vp, vp, vp, i32, i32, i64, f32, vp, vp, i32, vp, vp, i32, i32, vp, vp, vp]
     L.vs_dense_prefill.argtypes = [vp, vp, vp, i32, i32, i64, f32, vp, vp, vp]
+    L.vs_sparse_prefill_chunk.argtypes = [vp, vp, vp, i32, i32, i64, i64, i64, f32, vp, vp, i32, vp, vp, i32, i32, i32, vp, vp,
+                                          vp, sz, vp]
+    L.vs_dense_prefill_chunk.argtypes = [vp, vp, vp, i32, i32, i64, i64, i64, f32, vp, vp, vp]
+    L.vs_validate_lists.argtypes = [vp, vp, i32, i32, i64, vp, vp]
     L.vs_sparse_prefill_tiles.argtypes = [vp, sz, vp, ctypes.POINTER(ctypes.c_int64)]
     L.vs_aggregate_workspace.argtypes = [i32, i32, i32, i64]
     L.vs_aggregate_workspace.restype = sz
@@ -189,8 +193,13 @@ def sparse_prefill_workspace(q_heads, kv_heads, index_heads, n):
     return _load().vs_sparse_prefill_workspace(q_heads, kv_heads, index_heads, n)
 
 
-def sparse_prefill(q, k, v, idx_v, cnt_v, idx_s, cnt_s, o, lse, ws, scale=None, stream=None, slash_granularity=None):
+def sparse_prefill(q, k, v, idx_v, cnt_v, idx_s, cnt_s, o, lse, ws, scale=None, stream=None, slash_granularity=None,
+                   pos0=None):
+    """pos0 given: q / o hold a chunk of n_q rows at positions pos0 .. pos0 + n_q - 1, k / v all n_kv keys
+    (vs_sparse_prefill_chunk)."""
     import torch
+    if pos0 is not None:
+        return _sparse_prefill_chunk(q, k, v, idx_v, cnt_v, idx_s, cnt_s, o, lse, ws, scale, stream, slash_granularity or 1, pos0)
     _dev(q, torch.bfloat16, "q"); _dev(k, torch.bfloat16, "k"); _dev(v, torch.bfloat16, "v"); _dev(o, torch.bfloat16, "o")
     _dev(idx_v, torch.int32, "idx_v"); _dev(idx_s, torch.int32, "idx_s")
     _dev(cnt_v, torch.int32, "cnt_v"); _dev(cnt_s, torch.int32, "cnt_s")
@@ -214,6 +223,38 @@ def sparse_prefill(q, k, v, idx_v, cnt_v, idx_s, cnt_s, o, lse, ws, scale=None, 
                                                index_heads, int(slash_granularity), _ptr(o), _ptr(lse), _ptr(ws), ws_bytes,
                                                _stream(stream)), "vs_sparse_prefill_tiled")
     return o
+
+
+def _sparse_prefill_chunk(q, k, v, idx_v, cnt_v, idx_s, cnt_s, o, lse, ws, scale, stream, gran, pos0):
+    import torch
+    _dev(q, torch.bfloat16, "q"); _dev(k, torch.bfloat16, "k"); _dev(v, torch.bfloat16, "v"); _dev(o, torch.bfloat16, "o")
+    _dev(idx_v, torch.int32, "idx_v"); _dev(idx_s, torch.int32, "idx_s")
+    _dev(cnt_v, torch.int32, "cnt_v"); _dev(cnt_s, torch.int32, "cnt_s")
+    q_heads, n_q, d = q.shape
+    kv_heads, n_kv = k.shape[0], k.shape[1]
+    assert d == 128 and k.shape == (kv_heads, n_kv, 128) and v.shape == k.shape and o.shape == q.shape
+    index_heads = idx_v.shape[0]
+    assert idx_s.shape[0] == index_heads and cnt_v.numel() == index_heads and cnt_s.numel() == index_heads
+    if lse is not None:
+        _dev(lse, torch.float32, "lse")
+        assert lse.shape == (q_heads, n_q)
+    scale = 128 ** -0.5 if scale is None else scale
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    _check(_load().vs_sparse_prefill_chunk(_ptr(q), _ptr(k), _ptr(v), q_heads, kv_heads, n_q, n_kv, int(pos0), scale,
+                                           _ptr(idx_v), _ptr(cnt_v), idx_v.shape[1], _ptr(idx_s), _ptr(cnt_s),
+                                           idx_s.shape[1], index_heads, int(gran), _ptr(o), _ptr(lse), _ptr(ws), ws_bytes,
+                                           _stream(stream)), "vs_sparse_prefill_chunk")
+    return o
+
+
+def validate_lists(idx, cnt, n, report, stream=None):
+    """report [heads] int32 (device): 0 or a bit-or of 1 (bad count), 2 (entry out of range), 4 (not strictly ascending)."""
+    import torch
+    _dev(idx, torch.int32, "idx"); _dev(cnt, torch.int32, "cnt"); _dev(report, torch.int32, "report")
+    heads, cap = idx.shape
+    assert cnt.numel() == heads and report.numel() == heads
+    _check(_load().vs_validate_lists(_ptr(idx), _ptr(cnt), cap, heads, n, _ptr(report), _stream(stream)), "vs_validate_lists")
+    return report
 
 
 def sparse_prefill_static(q, k, v, idx_v, cnt_v, idx_s, cnt_s, o, lse, scale=None, stream=None):
@@ -279,15 +320,22 @@ def aggregate(q, k, a_v, a_s, ws, lse=None, lists=None, recall=None, scale=None,
     return a_v, a_s
 
 
-def dense_prefill(q, k, v, o, lse=None, scale=None, stream=None):
+def dense_prefill(q, k, v, o, lse=None, scale=None, stream=None, pos0=None):
+    """pos0 given: q / o hold a chunk of n_q rows at positions pos0 .. pos0 + n_q - 1 (vs_dense_prefill_chunk)."""
     import torch
     _dev(q, torch.bfloat16, "q"); _dev(k, torch.bfloat16, "k"); _dev(v, torch.bfloat16, "v"); _dev(o, torch.bfloat16, "o")
-    q_heads, n, d = q.shape
-    kv_heads = k.shape[0]
+    q_heads, n_q, d = q.shape
+    kv_heads, n = k.shape[0], k.shape[1]
     assert d == 128 and k.shape == (kv_heads, n, 128) and v.shape == k.shape and o.shape == q.shape
+    assert pos0 is not None or n_q == n
     if lse is not None:
         _dev(lse, torch.float32, "lse")
+        assert lse.shape == (q_heads, n_q)
     scale = 128 ** -0.5 if scale is None else scale
-    _check(_load().vs_dense_prefill(_ptr(q), _ptr(k), _ptr(v), q_heads, kv_heads, n, scale, _ptr(o), _ptr(lse),
-                                    _stream(stream)), "vs_dense_prefill")
+    if pos0 is None:
+        _check(_load().vs_dense_prefill(_ptr(q), _ptr(k), _ptr(v), q_heads, kv_heads, n, scale, _ptr(o), _ptr(lse),
+                                        _stream(stream)), "vs_dense_prefill")
+    else:
+        _check(_load().vs_dense_prefill_chunk(_ptr(q), _ptr(k), _ptr(v), q_heads, kv_heads, n_q, n, int(pos0), scale, _ptr(o),
+                                              _ptr(lse), _stream(stream)), "vs_dense_prefill_chunk")
     return o

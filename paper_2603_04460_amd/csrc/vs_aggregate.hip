@@ -418,7 +418,8 @@ int vs_aggregate(const void* q, const void* k, int q_heads, int kv_heads, int64_
     hipLaunchKernelGGL(fill_float_kernel, dim3(static_cast<unsigned>((out_count + 255) / 256)), dim3(256), 0, st, a_s, out_count, 0.f);
     VS_LAUNCH_CHECK();
     if (want_recall) {
-        hipLaunchKernelGGL(fill_float_kernel, dim3(1), dim3(256), 0, st, recall, static_cast<size_t>(out_heads), 0.f);
+        hipLaunchKernelGGL(fill_float_kernel, dim3(static_cast<unsigned>((out_heads + 255) / 256)), dim3(256), 0, st, recall,
+                           static_cast<size_t>(out_heads), 0.f);
         VS_LAUNCH_CHECK();
         uint32_t* sbit = reinterpret_cast<uint32_t*>(base + w.sbit_off);
         uint32_t* vbit = reinterpret_cast<uint32_t*>(base + w.vbit_off);

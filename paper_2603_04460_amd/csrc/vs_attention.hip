@@ -136,14 +136,15 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
     const int tile = p.tiles - 1 - rest / hchunks;          // longest tiles first
     const int BQ = 32 * kWaves / p.hc;
     const int nsub = BQ >> 5;
-    const int i0 = tile * BQ;
-    const int n = p.n;
-    const int i_last = min(i0 + BQ, n) - 1;
+    const int i0 = p.pos0 + tile * BQ;                      // positions are absolute; the tile grid starts at the chunk
+    const int n = p.n;                                      // keys
+    const int n_pos = p.pos0 + p.nq;                        // positions that exist
+    const int i_last = min(i0 + BQ, n_pos) - 1;
 
     // this wavefront's row block: 32 rows of one query head
     const int my_head = g * p.group + hchunk * p.hc + wave % p.hc;
     const int my_i0 = i0 + 32 * (wave / p.hc);
-    const bool my_rows = my_i0 < n;
+    const bool my_rows = my_i0 < n_pos;
     const int ih = p.index_per_q ? my_head : g;
     const uint32_t* __restrict__ vbit = p.vbit + static_cast<size_t>(ih) * p.vw;
 
@@ -154,11 +155,11 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
     bf16x8 qf[8];
     {
         const int row = my_i0 + qi;
-        const uint16_t* src = p.q + (static_cast<size_t>(my_head) * n + min(row, n - 1)) * kD + 8 * hh;
+        const uint16_t* src = p.q + (static_cast<size_t>(my_head) * p.nq + (min(row, n_pos - 1) - p.pos0)) * kD + 8 * hh;
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
             uint4 raw = make_uint4(0, 0, 0, 0);
-            if (row < n) raw = *reinterpret_cast<const uint4*>(src + 16 * kk);
+            if (row < n_pos) raw = *reinterpret_cast<const uint4*>(src + 16 * kk);
             qf[kk] = __builtin_bit_cast(bf16x8, raw);
         }
     }
@@ -289,7 +290,7 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
             // through a selected offset, i.e. if the window has a bit in [31 - kj, 62 - kj].
             // x bit s = OR of window bits s .. s+len-1, len = rows of this block that exist (32 except at the end of
             // the sequence): doubling up to the largest power of two pw <= len, then two overlapping windows
-            const int len = min(32, n - my_i0);
+            const int len = min(32, n_pos - my_i0);
             uint64_t x = ti.w;
             int pw = 1;
             while (2 * pw <= len) {
@@ -549,16 +550,16 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
             }
         // (only this wavefront touches its staging area: no barrier, the compiler orders the LDS accesses)
         const int srow = lane >> 4, schunk = lane & 15;
-        uint16_t* const obase = p.o + (static_cast<size_t>(my_head) * n + my_i0) * kD;
+        uint16_t* const obase = p.o + (static_cast<size_t>(my_head) * p.nq + (my_i0 - p.pos0)) * kD;
 #pragma unroll
         for (int it = 0; it < 8; ++it) {
             const int r = 4 * it + srow;
             const uint4 piece = *reinterpret_cast<const uint4*>(stage + r * kPitch + 16 * schunk);
-            if (my_i0 + r < n) *reinterpret_cast<uint4*>(obase + static_cast<size_t>(r) * kD + 8 * schunk) = piece;
+            if (my_i0 + r < n_pos) *reinterpret_cast<uint4*>(obase + static_cast<size_t>(r) * kD + 8 * schunk) = piece;
         }
         const int row = my_i0 + qi;
-        if (row < n && p.lse && hh == 0)
-            p.lse[static_cast<size_t>(my_head) * n + row] = l_tot > 0.f ? m_run * p.scale + __logf(l_tot) : NEG_INF;
+        if (row < n_pos && p.lse && hh == 0)
+            p.lse[static_cast<size_t>(my_head) * p.nq + (row - p.pos0)] = l_tot > 0.f ? m_run * p.scale + __logf(l_tot) : NEG_INF;
     }
     if (p.tile_counter && lane == 0 && tiles_done) atomicAdd(p.tile_counter, static_cast<unsigned long long>(tiles_done));
     if (!p.work_counter) break;
@@ -577,6 +578,7 @@ struct PrepParams {
     const int32_t* cnt_s;
     int cap_s;
     int n, nsub, nblk;
+    int shift;                      // pos0 % 32: row blocks start at positions 32 t + shift
     uint32_t* sbit;                 // per head: bit (o + 64) set iff offset o selected (64-bit zero guard in front, zero tail)
     uint32_t* vbit;
     int sw, vw;
@@ -587,14 +589,16 @@ struct PrepParams {
     int32_t* ncol32;
     int nq32;
     int32_t* vfirst;
-    uint32_t* counters;             // 64 words at the head of the workspace, zeroed here
+    uint32_t* counters;             // tile counter and the work queues' counters at the head of the workspace, zeroed here
+    int ncounters;
 };
 
 __global__ __launch_bounds__(kPrepThreads) void vs_prepare_kernel(const PrepParams p) {
     extern __shared__ __align__(16) uint32_t bm[];           // max(sw, vw) words, then 32 words of scan scratch
     const int ih = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     uint32_t* const scan = bm + max(p.sw, p.vw);
-    if (ih == 0 && tid < 64) p.counters[tid] = 0u;
+    if (ih == 0)
+        for (int i = tid; i < p.ncounters; i += kPrepThreads) p.counters[i] = 0u;
     // offsets
     for (int w = tid; w < p.sw; w += kPrepThreads) bm[w] = 0u;
     __syncthreads();
@@ -606,15 +610,17 @@ __global__ __launch_bounds__(kPrepThreads) void vs_prepare_kernel(const PrepPara
     __syncthreads();
     uint32_t* const sbit = p.sbit + static_cast<size_t>(ih) * p.sw;
     for (int w = tid; w < p.sw; w += kPrepThreads) sbit[w] = bm[w];
-    // Block diagonals.  Candidate c stands for delta = c - (nsub - 1); 32-row block t = delta + r of a query tile (r < nsub)
-    // crosses key block (tile's first block - delta) through the offsets 32 t - 31 .. 32 t + 31.  A thread owns a run
-    // of consecutive candidates; an exclusive scan of the per-thread counts gives the list positions.
+    // Block diagonals.  A query tile whose first row block starts at position 32 qb + shift looks, for diagonal delta, at
+    // key block qb - delta; its 32-row block r < nsub then sees that block through the offsets 32 (delta + r) + shift - 31
+    // .. + 31.  Candidate c stands for delta = c + dmin.  A thread owns a run of consecutive candidates; an exclusive
+    // scan of the per-thread counts gives the list positions.
     const int nsub = p.nsub;
-    const int ncand = p.nblk + nsub - 1;
+    const int dmin = -(nsub - 1) - (p.shift > 0 ? 1 : 0);
+    const int ncand = p.nblk - dmin;
     const int per = (ncand + kPrepThreads - 1) / kPrepThreads;
     const int c0 = min(tid * per, ncand), c1 = min(c0 + per, ncand);
-    auto window = [&](int t) -> uint64_t {                   // offsets 32 t - 31 .. 32 t + 31 at bits 0..62
-        return t < 0 ? 0ull : (window64(bm, 32 * t + 33) & kAll63);
+    auto window = [&](int t) -> uint64_t {                   // offsets 32 t + shift - 31 .. 32 t + shift + 31 at bits 0..62
+        return 32 * t + p.shift + 31 < 0 ? 0ull : (window64(bm, 32 * t + p.shift + 33) & kAll63);
     };
     auto crossed = [&](int delta) -> bool {
         uint64_t any = 0ull;
@@ -622,7 +628,7 @@ __global__ __launch_bounds__(kPrepThreads) void vs_prepare_kernel(const PrepPara
         return any != 0ull;
     };
     int mine = 0;
-    for (int c = c0; c < c1; ++c) mine += crossed(c - (nsub - 1)) ? 1 : 0;
+    for (int c = c0; c < c1; ++c) mine += crossed(c + dmin) ? 1 : 0;
     int incl = mine;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
@@ -637,7 +643,7 @@ __global__ __launch_bounds__(kPrepThreads) void vs_prepare_kernel(const PrepPara
     unsigned long long* const wl = p.wlist + static_cast<size_t>(ih) * p.dcap * 4;
     int32_t* const nd = p.ndiag + static_cast<size_t>(ih) * p.nq32;
     for (int c = c0; c < c1; ++c) {
-        const int delta = c - (nsub - 1);
+        const int delta = c + dmin;
         if (crossed(delta)) {
             dl[pos] = delta;
             for (int r = 0; r < 4; ++r) wl[static_cast<size_t>(pos) * 4 + r] = r < nsub ? window(delta + r) : 0ull;
@@ -676,7 +682,7 @@ struct SparseWs {
     int sw, vw, nq32, dcap;
 };
 
-SparseWs sparse_ws_layout(int index_heads, int64_t n) {
+SparseWs sparse_ws_layout(int kv_heads, int index_heads, int64_t n) {
     SparseWs w;
     const int64_t nblk = (n + 31) / 32;
     const size_t ih = static_cast<size_t>(index_heads);
@@ -684,8 +690,8 @@ SparseWs sparse_ws_layout(int index_heads, int64_t n) {
     w.vw = static_cast<int>(vs::round_up(static_cast<size_t>(nblk + 4), 4));
     w.nq32 = static_cast<int>(nblk);
     w.dcap = static_cast<int>(nblk + 4);
-    w.counter_off = 0;
-    w.sbit_off = 256;
+    w.counter_off = 0;                                      // 8 bytes of tile counter, then from byte 64 one counter per KV head
+    w.sbit_off = vs::round_up(64 + static_cast<size_t>(kv_heads) * 4, 256);
     w.vbit_off = w.sbit_off + ih * w.sw * 4;
     w.ncol_off = vs::round_up(w.vbit_off + ih * w.vw * 4, 256);
     w.ndiag_off = vs::round_up(w.ncol_off + ih * w.nq32 * 4, 256);
@@ -738,7 +744,7 @@ int launch_attention(AttnParams& p, hipStream_t stream) {
     const int rc = device_info(info);
     if (rc != VS_OK) return rc;
     const int BQ = 32 * kWaves / p.hc;
-    p.tiles = (p.n + BQ - 1) / BQ;
+    p.tiles = (p.nq + BQ - 1) / BQ;
     const long long blocks = static_cast<long long>(p.kv_heads) * (p.group / p.hc) * p.tiles;
     if (blocks > 0x7fffffffLL) return VS_ERR_UNSUPPORTED;
     p.work_total = static_cast<int>(blocks);
@@ -751,7 +757,7 @@ int launch_attention(AttnParams& p, hipStream_t stream) {
 
 // Runs the whole sparse call on a workspace that is known to be large enough.
 int sparse_prefill_on(unsigned char* base, const SparseWs& w, const void* q, const void* k, const void* v, int q_heads,
-                      int kv_heads, int64_t n, float scale, const int32_t* idx_v, const int32_t* cnt_v, int cap_v,
+                      int kv_heads, int64_t nq, int64_t n, int64_t pos0, float scale, const int32_t* idx_v, const int32_t* cnt_v, int cap_v,
                       const int32_t* idx_s, const int32_t* cnt_s, int cap_s, int index_heads, int slash_granularity,
                       void* o_bf16, float* lse, hipStream_t st) {
     AttnParams p{};
@@ -767,6 +773,8 @@ int sparse_prefill_on(unsigned char* base, const SparseWs& w, const void* q, con
     p.hc = heads_per_workgroup(p.group, p.index_per_q != 0);
     p.gran = slash_granularity;
     p.n = static_cast<int>(n);
+    p.nq = static_cast<int>(nq);
+    p.pos0 = static_cast<int>(pos0);
     p.scale = scale;
     p.c = scale * 1.4426950408889634f;
     p.idx_v = idx_v;
@@ -782,9 +790,8 @@ int sparse_prefill_on(unsigned char* base, const SparseWs& w, const void* q, con
     p.nq32 = w.nq32;
     p.vfirst = reinterpret_cast<const int32_t*>(base + w.vfirst_off);
     p.tile_counter = reinterpret_cast<unsigned long long*>(base + w.counter_off);
-    // one queue counter per KV head at bytes 128.. of the counter block (zeroed by the preparation kernel); more than 32
-    // KV heads do not fit there: one workgroup per unit then
-    p.work_counter = kv_heads <= 32 ? reinterpret_cast<unsigned int*>(base + w.counter_off + 128) : nullptr;
+    // one queue counter per KV head from byte 64 of the counter block (zeroed by the preparation kernel)
+    p.work_counter = reinterpret_cast<unsigned int*>(base + w.counter_off + 64);
 
     DeviceInfo info;
     int rc = device_info(info);
@@ -799,6 +806,7 @@ int sparse_prefill_on(unsigned char* base, const SparseWs& w, const void* q, con
     pp.n = p.n;
     pp.nsub = kWaves / p.hc;
     pp.nblk = w.nq32;
+    pp.shift = static_cast<int>(pos0 % 32);
     pp.sbit = reinterpret_cast<uint32_t*>(base + w.sbit_off);
     pp.vbit = reinterpret_cast<uint32_t*>(base + w.vbit_off);
     pp.sw = w.sw;
@@ -811,6 +819,7 @@ int sparse_prefill_on(unsigned char* base, const SparseWs& w, const void* q, con
     pp.nq32 = w.nq32;
     pp.vfirst = reinterpret_cast<int32_t*>(base + w.vfirst_off);
     pp.counters = reinterpret_cast<uint32_t*>(base + w.counter_off);
+    pp.ncounters = 16 + kv_heads;
     const size_t prep_lds = (static_cast<size_t>(w.sw > w.vw ? w.sw : w.vw) + 32) * 4;
     if (prep_lds > 160 * 1024) return VS_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(vs_prepare_kernel, dim3(index_heads), dim3(kPrepThreads), prep_lds, st, pp);
@@ -825,30 +834,41 @@ extern "C" {
 size_t vs_sparse_prefill_workspace(int q_heads, int kv_heads, int index_heads, int64_t n) {
     if (q_heads <= 0 || kv_heads <= 0 || n <= 0 || n > VS_MAX_SEQ) return 0;
     if (index_heads != q_heads && index_heads != kv_heads) return 0;
-    return sparse_ws_layout(index_heads, n).total;
+    return sparse_ws_layout(kv_heads, index_heads, n).total;
 }
 
 int vs_sparse_prefill(const void* q, const void* k, const void* v, int q_heads, int kv_heads, int64_t n, float scale,
                       const int32_t* idx_v, const int32_t* cnt_v, int cap_v, const int32_t* idx_s, const int32_t* cnt_s,
                       int cap_s, int index_heads, void* o_bf16, float* lse, void* ws, size_t ws_bytes, void* stream) {
-    return vs_sparse_prefill_tiled(q, k, v, q_heads, kv_heads, n, scale, idx_v, cnt_v, cap_v, idx_s, cnt_s, cap_s, index_heads,
-                                   1, o_bf16, lse, ws, ws_bytes, stream);
+    return vs_sparse_prefill_chunk(q, k, v, q_heads, kv_heads, n, n, 0, scale, idx_v, cnt_v, cap_v, idx_s, cnt_s, cap_s,
+                                   index_heads, 1, o_bf16, lse, ws, ws_bytes, stream);
 }
 
 int vs_sparse_prefill_tiled(const void* q, const void* k, const void* v, int q_heads, int kv_heads, int64_t n, float scale,
                             const int32_t* idx_v, const int32_t* cnt_v, int cap_v, const int32_t* idx_s,
                             const int32_t* cnt_s, int cap_s, int index_heads, int slash_granularity, void* o_bf16,
                             float* lse, void* ws, size_t ws_bytes, void* stream) {
-    int rc = check_qkv(q, k, v, q_heads, kv_heads, n, scale, o_bf16);
+    return vs_sparse_prefill_chunk(q, k, v, q_heads, kv_heads, n, n, 0, scale, idx_v, cnt_v, cap_v, idx_s, cnt_s, cap_s,
+                                   index_heads, slash_granularity, o_bf16, lse, ws, ws_bytes, stream);
+}
+
+int vs_sparse_prefill_chunk(const void* q, const void* k, const void* v, int q_heads, int kv_heads, int64_t n_q, int64_t n_kv,
+                            int64_t pos0, float scale, const int32_t* idx_v, const int32_t* cnt_v, int cap_v,
+                            const int32_t* idx_s, const int32_t* cnt_s, int cap_s, int index_heads, int slash_granularity,
+                            void* o_bf16, float* lse, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_qkv(q, k, v, q_heads, kv_heads, n_kv, scale, o_bf16);
+    if (rc != VS_OK) return rc;
+    rc = check_chunk(n_q, n_kv, pos0);
     if (rc != VS_OK) return rc;
     if (slash_granularity != 1 && slash_granularity != 32) return VS_ERR_UNSUPPORTED;
+    if (slash_granularity == 32 && pos0 % 32 != 0) return VS_ERR_UNSUPPORTED;   // aligned 32-position blocks
     if (!idx_v || !cnt_v || !idx_s || !cnt_s || cap_v <= 0 || cap_s <= 0) return VS_ERR_INVALID_ARG;
     if (index_heads != q_heads && index_heads != kv_heads) return VS_ERR_INVALID_ARG;
-    const SparseWs w = sparse_ws_layout(index_heads, n);
+    const SparseWs w = sparse_ws_layout(kv_heads, index_heads, n_kv);
     if (!ws || ws_bytes < w.total) return VS_ERR_WORKSPACE;
     if (!vs::aligned16(ws)) return VS_ERR_INVALID_ARG;
-    return sparse_prefill_on(static_cast<unsigned char*>(ws), w, q, k, v, q_heads, kv_heads, n, scale, idx_v, cnt_v, cap_v,
-                             idx_s, cnt_s, cap_s, index_heads, slash_granularity, o_bf16, lse,
+    return sparse_prefill_on(static_cast<unsigned char*>(ws), w, q, k, v, q_heads, kv_heads, n_q, n_kv, pos0, scale, idx_v,
+                             cnt_v, cap_v, idx_s, cnt_s, cap_s, index_heads, slash_granularity, o_bf16, lse,
                              static_cast<hipStream_t>(stream));
 }
 
@@ -859,14 +879,14 @@ int vs_sparse_prefill_static(const void* q, const void* k, const void* v, int q_
     if (rc != VS_OK) return rc;
     if (!idx_v || !cnt_v || !idx_s || !cnt_s || cap_v <= 0 || cap_s <= 0) return VS_ERR_INVALID_ARG;
     if (index_heads != q_heads && index_heads != kv_heads) return VS_ERR_INVALID_ARG;
-    const SparseWs w = sparse_ws_layout(index_heads, n);
+    const SparseWs w = sparse_ws_layout(kv_heads, index_heads, n);
     if (w.total > kStaticScratchBytes) return VS_ERR_STATIC_LIMIT;
     DeviceInfo info;
     rc = device_info(info);
     if (rc != VS_OK) return rc;
     // every structure the kernels read is rewritten by the preparation kernel of this call (counters included), so what
     // the previous call left in the array does not matter
-    return sparse_prefill_on(info.scratch_ptr, w, q, k, v, q_heads, kv_heads, n, scale, idx_v, cnt_v, cap_v, idx_s, cnt_s,
+    return sparse_prefill_on(info.scratch_ptr, w, q, k, v, q_heads, kv_heads, n, n, 0, scale, idx_v, cnt_v, cap_v, idx_s, cnt_s,
                              cap_s, index_heads, 1, o_bf16, lse, static_cast<hipStream_t>(stream));
 }
 

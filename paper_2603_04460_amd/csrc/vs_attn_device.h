@@ -37,7 +37,8 @@ struct AttnParams {
     const uint16_t* v;
     uint16_t* o;
     float* lse;
-    int q_heads, kv_heads, group, hc, n, tiles, index_per_q;
+    int q_heads, kv_heads, group, hc, n, tiles, index_per_q;   // n: keys per head
+    int nq, pos0;                   // query rows per head; row r is position pos0 + r (pos0 + nq <= n)
     int gran;                       // slash granularity: 1 (element-exact) or 32 (per 32-row block)
     float scale, c;                 // c = scale * log2(e)
     const int32_t* idx_v;
@@ -123,6 +124,12 @@ __device__ __forceinline__ void lds_load16s(uint32_t voff, const void* sbase, co
     const uint32_t base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
         (const __attribute__((address_space(3))) void*)lds_base));
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(base), "v"(voff), "s"(sbase) : "memory", "m0");
+}
+
+// chunk: nq query rows at positions pos0 .. pos0 + nq - 1 against n keys
+int check_chunk(int64_t nq, int64_t n, int64_t pos0) {
+    if (nq <= 0 || pos0 < 0 || pos0 + nq > n) return VS_ERR_INVALID_ARG;
+    return VS_OK;
 }
 
 int check_qkv(const void* q, const void* k, const void* v, int q_heads, int kv_heads, int64_t n, float scale, void* o) {

@@ -49,9 +49,10 @@ __global__ __launch_bounds__(kThreads) void vs_dense_kernel(const AttnParams p) 
     const int hchunk = rest % hchunks;
     const int tile = p.tiles - 1 - rest / hchunks;          // longest tiles first
     const int BQ = 256 / p.hc;
-    const int i0 = tile * BQ;
-    const int n = p.n;
-    const int i_last = min(i0 + BQ, n) - 1;
+    const int i0 = p.pos0 + tile * BQ;                      // positions are absolute; the tile grid starts at the chunk
+    const int n = p.n;                                      // keys
+    const int n_pos = p.pos0 + p.nq;                        // positions that exist
+    const int i_last = min(i0 + BQ, n_pos) - 1;
 
     int my_head[2], my_i0[2];
     bool my_rows[2];
@@ -60,7 +61,7 @@ __global__ __launch_bounds__(kThreads) void vs_dense_kernel(const AttnParams p) 
         const int w = 2 * wave + rb;
         my_head[rb] = g * p.group + hchunk * p.hc + w % p.hc;
         my_i0[rb] = i0 + 32 * (w / p.hc);
-        my_rows[rb] = my_i0[rb] < n;
+        my_rows[rb] = my_i0[rb] < n_pos;
     }
     const uint16_t* __restrict__ kbase = p.k + static_cast<size_t>(g) * n * kD;
     const uint16_t* __restrict__ vbase = p.v + static_cast<size_t>(g) * n * kD;
@@ -69,11 +70,11 @@ __global__ __launch_bounds__(kThreads) void vs_dense_kernel(const AttnParams p) 
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
         const int row = my_i0[rb] + qi;
-        const uint16_t* src = p.q + (static_cast<size_t>(my_head[rb]) * n + min(row, n - 1)) * kD + 8 * hh;
+        const uint16_t* src = p.q + (static_cast<size_t>(my_head[rb]) * p.nq + (min(row, n_pos - 1) - p.pos0)) * kD + 8 * hh;
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
             uint4 raw = make_uint4(0, 0, 0, 0);
-            if (row < n) raw = *reinterpret_cast<const uint4*>(src + 16 * kk);
+            if (row < n_pos) raw = *reinterpret_cast<const uint4*>(src + 16 * kk);
             qf[rb][kk] = __builtin_bit_cast(bf16x8, raw);
         }
     }
@@ -373,8 +374,8 @@ __global__ __launch_bounds__(kThreads) void vs_dense_kernel(const AttnParams p) 
         const float l_tot = half_swap_sum(l_run[rb]);
         const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
         const int row = my_i0[rb] + qi;
-        if (row < n) {
-            uint16_t* dst = p.o + (static_cast<size_t>(my_head[rb]) * n + row) * kD;
+        if (row < n_pos) {
+            uint16_t* dst = p.o + (static_cast<size_t>(my_head[rb]) * p.nq + (row - p.pos0)) * kD;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -389,20 +390,21 @@ __global__ __launch_bounds__(kThreads) void vs_dense_kernel(const AttnParams p) 
                     *reinterpret_cast<uint2*>(dst + 32 * db + 8 * a + 4 * hh) = out;
                 }
             if (p.lse && hh == 0)
-                p.lse[static_cast<size_t>(my_head[rb]) * n + row] = l_tot > 0.f ? m_run[rb] * p.scale + __logf(l_tot) : NEG_INF;
+                p.lse[static_cast<size_t>(my_head[rb]) * p.nq + (row - p.pos0)] = l_tot > 0.f ? m_run[rb] * p.scale + __logf(l_tot) : NEG_INF;
         }
     }
 }
 
 int launch_dense(AttnParams& p, hipStream_t stream) {
-    static bool attr_set = false;
-    if (!attr_set) {
+    static vs::PerDeviceOnce once;
+    const int rc_once = once.run(nullptr, [](int) -> int {
         VS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&vs_dense_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                    static_cast<int>(kSmemBytes)));
-        attr_set = true;
-    }
+        return VS_OK;
+    });
+    if (rc_once != VS_OK) return rc_once;
     const int BQ = 256 / p.hc;
-    p.tiles = (p.n + BQ - 1) / BQ;
+    p.tiles = (p.nq + BQ - 1) / BQ;
     // one workgroup per (query tile, KV head, chunk of the group's heads), longest tiles first; workgroups are dealt
     // to the 8 XCDs round-robin, so KV head = block % kv_heads keeps a head's K / V in one XCD's L2
     const long long blocks = static_cast<long long>(p.kv_heads) * (p.group / p.hc) * p.tiles;
@@ -415,9 +417,13 @@ int launch_dense(AttnParams& p, hipStream_t stream) {
 
 }  // namespace
 
-extern "C" int vs_dense_prefill(const void* q, const void* k, const void* v, int q_heads, int kv_heads, int64_t n, float scale,
-                                void* o_bf16, float* lse, void* stream) {
-    int rc = check_qkv(q, k, v, q_heads, kv_heads, n, scale, o_bf16);
+extern "C" {
+
+int vs_dense_prefill_chunk(const void* q, const void* k, const void* v, int q_heads, int kv_heads, int64_t n_q, int64_t n_kv,
+                           int64_t pos0, float scale, void* o_bf16, float* lse, void* stream) {
+    int rc = check_qkv(q, k, v, q_heads, kv_heads, n_kv, scale, o_bf16);
+    if (rc != VS_OK) return rc;
+    rc = check_chunk(n_q, n_kv, pos0);
     if (rc != VS_OK) return rc;
     AttnParams p{};
     p.q = static_cast<const uint16_t*>(q);
@@ -430,9 +436,18 @@ extern "C" int vs_dense_prefill(const void* q, const void* k, const void* v, int
     p.group = q_heads / kv_heads;
     p.index_per_q = 0;
     p.hc = heads_per_workgroup(p.group, false);
-    p.n = static_cast<int>(n);
+    p.n = static_cast<int>(n_kv);
+    p.nq = static_cast<int>(n_q);
+    p.pos0 = static_cast<int>(pos0);
     p.scale = scale;
     p.c = scale * 1.4426950408889634f;
     p.tile_counter = nullptr;
     return launch_dense(p, static_cast<hipStream_t>(stream));
 }
+
+int vs_dense_prefill(const void* q, const void* k, const void* v, int q_heads, int kv_heads, int64_t n, float scale,
+                     void* o_bf16, float* lse, void* stream) {
+    return vs_dense_prefill_chunk(q, k, v, q_heads, kv_heads, n, n, 0, scale, o_bf16, lse, stream);
+}
+
+}  // extern "C"

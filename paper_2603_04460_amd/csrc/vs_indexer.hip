@@ -286,14 +286,15 @@ int vs_index_score(const void* k_bf16, const void* v_bf16, int kv_heads, int64_t
     uint16_t* hi = reinterpret_cast<uint16_t*>(static_cast<unsigned char*>(ws) + lay.hi_off);
     uint16_t* lo = reinterpret_cast<uint16_t*>(static_cast<unsigned char*>(ws) + lay.lo_off);
 
-    static bool attr_set = false;
-    if (!attr_set) {
+    static vs::PerDeviceOnce once;
+    const int rc_once = once.run(nullptr, [](int) -> int {
         VS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&indexer_logits_kernel<0>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kSmemBytes)));
         VS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&indexer_logits_kernel<1>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kSmemBytes)));
-        attr_set = true;
-    }
+        return VS_OK;
+    });
+    if (rc_once != VS_OK) return rc_once;
     hipLaunchKernelGGL(split_weights_kernel, dim3((w->d_h * 256 + 255) / 256), dim3(256), 0, st, w->W_U, w->d_h, hi, lo);
     VS_LAUNCH_CHECK();
     float2* part = reinterpret_cast<float2*>(static_cast<unsigned char*>(ws) + lay.part_off);

@@ -160,6 +160,15 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelParams p) 
                     __syncthreads();
                     return pk;
                 }
+                if (trem > total) {
+                    // Totals above 2^53 are rounded when they become a double, so ceil(tau * total) can exceed the total
+                    // itself (tau = 1, more than 2^13 saturated scores): the mass is then never reached and the rule
+                    // keeps every element.  Crossing value 0 with every tie taken says exactly that.
+                    pk.vstar = 0u;
+                    pk.ties = 0xffffffffu;
+                    __syncthreads();
+                    return pk;
+                }
             }
             u64 mrun = mbase + mi - msum;
             uint32_t crun = cbase + ci - csum;

@@ -3,8 +3,8 @@
 are not available; the structure follows the paper's description of real attention (heavy-hitter
 columns, a strong near-diagonal band, discrete long-range offset bands).
 
-This module holds input recipes only: no RoPE, no indexer, no selection, no attention.  Both the
-GPU path and the CPU oracle are fed from here.
+This module holds input recipes only: no RoPE, no indexer, no selection, no attention.  It belongs to
+neither the library nor the oracle: the tests, the benchmark and the smoke check feed both from here.
 """
 import numpy as np
 import torch

@@ -4,7 +4,7 @@ import numpy as np
 import torch
 
 import paper_2603_04460_amd as vs
-from paper_2603_04460_amd import synth
+import synth
 
 ATTN_ATOL = 2e-2      # max-abs on bf16 attention outputs (fp32 accumulation), the bar of the benchmark spec
 SCORE_RTOL = 1e-3     # indexer scores, relative

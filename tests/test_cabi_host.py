@@ -104,7 +104,7 @@ def test_product_path_does_not_import_the_oracle():
 
 def test_synth_generators_are_seeded_and_shaped():
     import numpy as np
-    from paper_2603_04460_amd import synth
+    import synth
     q1, k1, v1 = synth.qkv(7, 8, 2, 256, local_structure=True)
     q2, k2, v2 = synth.qkv(7, 8, 2, 256, local_structure=True)
     assert q1.shape == (8, 256, 128) and k1.shape == (2, 256, 128)

@@ -7,7 +7,7 @@ import pytest
 import torch
 
 import paper_2603_04460_amd as vs
-from paper_2603_04460_amd import synth
+import synth
 from oracle import vs_oracle as oracle
 from gpu_util import make_qkv, lists, run_dense
 

@@ -6,7 +6,7 @@ import torch
 
 import oracle
 import paper_2603_04460_amd as vs
-from paper_2603_04460_amd import synth
+import synth
 from gpu_util import make_qkv, run_sparse, run_dense, lists, check_attention, check_key_set, bf16_to_f64
 
 pytestmark = pytest.mark.gpu

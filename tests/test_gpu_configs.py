@@ -12,7 +12,7 @@ import torch
 
 import oracle
 import paper_2603_04460_amd as vs
-from paper_2603_04460_amd import synth
+import synth
 import bench
 from gpu_util import check_attention, check_key_set
 

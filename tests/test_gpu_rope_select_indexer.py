@@ -6,7 +6,7 @@ import torch
 
 import oracle
 import paper_2603_04460_amd as vs
-from paper_2603_04460_amd import synth
+import synth
 
 pytestmark = pytest.mark.gpu
 
@@ -100,6 +100,19 @@ def test_select_bad_scores_and_errors():
     with pytest.raises(vs.VsError) as e:
         _gpu_select(a, a, vs.Budget(mode=0, tau_v=0.5, tau_s=0.5, n_sink=10, cap_v=4, cap_s=n))
     assert e.value.code == -4
+
+
+def test_select_threshold_above_rounded_total():
+    """tau = 1 with more than 2^13 saturated scores: the total mass (2^53 + 2^40 + 3) is not a double, ceil(tau * total)
+    rounds above the total, the mass is never reached and the rule keeps everything (k = n), as the oracle does."""
+    n = (1 << 13) + 1 + 3
+    a = np.full((1, n), 2.0, dtype=np.float32)              # saturated: mass 2^40 each
+    a[0, [100, 5000, n - 1]] = 2.0 ** -40                   # mass 1 each
+    ref = oracle.select(a, 0, 1.0, 0, 0, n)
+    assert ref[3][0] == n and ref[1][0] == n                # the oracle's k and count
+    _check_select(a, a.copy(), vs.Budget(mode=0, tau_v=1.0, tau_s=1.0, n_sink=0, n_local=1, cap_v=n, cap_s=n))
+    # and with a capacity below n: forced entries + best-ranked others, overflow flagged
+    _check_select(a, a.copy(), vs.Budget(mode=0, tau_v=1.0, tau_s=1.0, n_sink=2, n_local=3, cap_v=1000, cap_s=77))
 
 
 # ---------------------------------------------------------------- indexer

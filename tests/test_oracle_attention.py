@@ -340,3 +340,83 @@ def test_tile_granular_matches_definition_and_contains_exact(n, g, seed):
     assert np.all(np.isfinite(M)[exact])                     # superset of the element-exact mask
     if g == 1:
         assert np.array_equal(np.isfinite(M), exact)
+
+
+# ---------------------------------------------------------------- chunked prefill (query rows at positions pos0 ..)
+@pytest.mark.parametrize("name,pos0", [("vs_mask_n8_a.txt", 5), ("vs_mask_n8_b.txt", 3), ("vs_mask_n8_a.txt", 0)])
+def test_chunk_hand_worked_split(name, pos0):
+    """The hand-worked 8-token examples, split: the chunk holding positions pos0 .. 7 must keep, for each of its rows,
+    exactly the keys the fixture lists for that position (q = 0: the output is the mean of V over them)."""
+    n, I_v, I_s, rows = _read_gold(name)
+    d = 4
+    k = rand_bits(np.random.default_rng(0), 1, n, d)
+    vf = (np.arange(n)[:, None] * 1.0 + np.array([0.0, 16.0, 32.0, 64.0])[None, :]).astype(np.float32)
+    v = f32_to_bf16_bits(vf)[None]
+    q = np.zeros((1, n - pos0, d), dtype=np.uint16)
+    iv, cv = lists(I_v)
+    is_, cs = lists(I_s)
+    out, lse, live = oracle.sparse_attention(q, k, v, iv, cv, is_, cs, return_live=True, pos0=pos0)
+    assert out.shape == (1, n - pos0, d)
+    for r in range(n - pos0):
+        keys = rows[pos0 + r]
+        assert live[0, r] == len(keys)
+        np.testing.assert_allclose(out[0, r], vf[keys].astype(np.float64).mean(axis=0), atol=1e-12)
+        np.testing.assert_allclose(lse[0, r], np.log(len(keys)), atol=1e-12)
+
+
+def test_chunk_aligned_blocks_of_absolute_positions():
+    """Tile-granular chunk: blocks are aligned in absolute positions, so a chunk that starts inside a block (pos0 = 6, g = 4)
+    keeps for positions 6 and 7 what the fixture lists for them (their block is {4..7}, offset 6 reaches keys 0 and 1)."""
+    n, I_v, I_s, rows = _read_gold("vs_mask_n12_g4.txt")
+    d, pos0 = 4, 6
+    k = rand_bits(np.random.default_rng(3), 1, n, d)
+    vf = (np.arange(n)[:, None] + np.array([0.0, 16.0, 32.0, 64.0])[None, :]).astype(np.float32)
+    v = f32_to_bf16_bits(vf)[None]
+    q = np.zeros((1, n - pos0, d), dtype=np.uint16)
+    iv, cv = lists(I_v, cap=1)
+    is_, cs = lists(I_s)
+    out, _, live = oracle.sparse_attention(q, k, v, iv, cv, is_, cs, return_live=True, granularity=4, pos0=pos0)
+    for r in range(n - pos0):
+        assert live[0, r] == len(rows[pos0 + r])
+        np.testing.assert_allclose(out[0, r], vf[rows[pos0 + r]].astype(np.float64).mean(axis=0), atol=1e-12)
+
+
+@pytest.mark.parametrize("g", [1, 4])
+def test_chunks_equal_full_call_and_brute_force(g):
+    """Any split of a sequence into chunks reproduces the rows of the full call (same arithmetic per row: identical);
+    a chunk also matches the numpy mask written for its absolute positions; keys past the chunk's last position do not
+    matter."""
+    rng = np.random.default_rng(40 + g)
+    n, d, hq, hk = 50, 8, 4, 2
+    q, k, v = rand_bits(rng, hq, n, d), rand_bits(rng, hk, n, d), rand_bits(rng, hk, n, d)
+    sv = [rng.choice(n, size=5, replace=False) for _ in range(hk)]
+    ss = [np.concatenate([[0], rng.choice(np.arange(1, n), size=6, replace=False)]) for _ in range(hk)]
+    iv, cv = lists(*sv)
+    is_, cs = lists(*ss)
+    full, full_lse = oracle.sparse_attention(q, k, v, iv, cv, is_, cs, granularity=g)
+    dfull, dfull_lse = oracle.dense_attention(q, k, v)
+    for bounds in ([0, 13, 32, 50], [0, 49, 50], [0, 50]):
+        if g > 1 and any(b % g for b in bounds[:-1]):
+            continue                                       # a chunk boundary inside a block changes which positions exist
+        for a, b in zip(bounds[:-1], bounds[1:]):
+            out, lse = oracle.sparse_attention(q[:, a:b], k, v, iv, cv, is_, cs, granularity=g, pos0=a) if g == 1 else \
+                oracle.sparse_attention(q[:, a:b], k[:, :b], v[:, :b], iv, cv, is_, cs, granularity=g, pos0=a)
+            if g == 1 or b == n:
+                np.testing.assert_array_equal(out, full[:, a:b])
+                np.testing.assert_array_equal(lse, full_lse[:, a:b])
+            do, dl = oracle.dense_attention(q[:, a:b], k, v, pos0=a)
+            np.testing.assert_array_equal(do, dfull[:, a:b])
+            np.testing.assert_array_equal(dl, dfull_lse[:, a:b])
+    # brute force for one chunk, written for absolute positions
+    a, b = 13, 32
+    out, lse = oracle.sparse_attention(q[:, a:b], k, v, iv, cv, is_, cs, granularity=g, pos0=a)
+    for h in range(hq):
+        gk = h // (hq // hk)
+        M = _granular_mask(b, sv[gk], ss[gk], g)[a:b]      # the sequence ends at the chunk's last position
+        Mfull = np.full((b - a, n), -np.inf)
+        Mfull[:, :b] = M
+        P = bits_to_f64(q[h, a:b]) @ bits_to_f64(k[gk]).T / np.sqrt(d) + Mfull       # [chunk rows, all keys]
+        mx = P.max(axis=1, keepdims=True)
+        E = np.exp(P - mx)
+        np.testing.assert_allclose(out[h], (E / E.sum(axis=1, keepdims=True)) @ bits_to_f64(v[gk]), atol=1e-12)
+        np.testing.assert_allclose(lse[h], mx[:, 0] + np.log(E.sum(axis=1)), atol=1e-12)
