@@ -5,16 +5,28 @@ A step is one pass of the whole path over one layer: VSIndexer scoring -> cumula
 with TopK -> fused causal vertical-slash sparse attention.  Inputs are synthetic (seeded, shaped like a
 4B-model GQA layer: 32 query heads, 8 KV heads, head_dim 128) and resident in HBM before timing starts.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--n 131072] [--tau 0.9] [--config 4|5]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--n N] [--tau T]
+                    [--structure planted|plain] [--white] [--sweep]
 
-Prints ONE JSON line.  `value` is the dense-equivalent effective TFLOP/s of the whole step
-(32 * 2 n^2 * 128 flop of dense causal attention divided by the step time); ms/layer, the per-stage split,
-the speedup over the in-library dense causal kernel, the MFMA roofline of the attention kernel and the CPU
-oracle baseline ride along.
+Workloads (the five configurations of the baseline; the default is 4):
+  1  one head, n = 4096, fixed index lists (4 sink + 60 random columns, 64 local + 64 random offsets): attention only
+  2  32 / 8 heads, n = 32768, planted heavy hitters, fixed budget 1024 columns + 2048 offsets chosen by vs_select_budget
+     from seeded score vectors (structured; --white: unstructured scores, the worst case for tile coverage):
+     selection + attention
+  3  the whole pipeline at n = 65536 on unstructured inputs (N(0,1) tensors, random-init indexer, nothing planted)
+  4  the whole pipeline at n = 131072, heavy hitters + local structure + planted score bands (--structure plain: the same
+     tensors without the planted score bands), tau from --tau
+  5  as 4 with RoPE base 5e5
+
+Prints ONE JSON line.  `value` is the dense-equivalent effective TFLOP/s of the whole step (q_heads * 2 n^2 * 128 flop
+of dense causal attention divided by the step time); ms/layer, the per-stage split with each stage's own roofline, the
+speedup over the in-library dense causal kernel, the MFMA roofline of the attention kernel and the CPU oracle baseline
+ride along.
 """
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -28,54 +40,104 @@ import paper_2603_04460_amd as vs  # noqa: E402
 import synth  # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0           # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0               # MI355X HBM3E
 FLOP_PER_TILE = 4 * 128 * 32 * 32   # QK^T and PV of a 32-row x 32-key tile at head_dim 128
-# HBM bytes per launch of the sparse attention kernel at the default workload (C4, n = 131072, tau = 0.9), from the
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/c4_128k_hbm_counters.txt:
-# 2001626.9 KiB fetched x 0.99998 (plain-copy calibration) + 1316964.3 KiB written.  Other workloads report null.
-MEASURED_TRAFFIC_BYTES = 3398196395
+STAGED_TILE_BYTES = 2 * 32 * 256    # K and V rows of one 32-key tile
+# HBM bytes per launch of the sparse attention kernel at the default workload come from the hardware-counter summary
+# committed beside the kernel-trace profile of the same command (never from this process): the file states how it was made.
+TRAFFIC_PROFILE = os.path.join("profiles", "c4_128k_hbm_counters.txt")
+DEFAULT_N = {1: 4096, 2: 32768, 3: 65536, 4: 131072, 5: 131072}
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-class Workload:
-    """Config 4 / 5 of the baseline: one GQA layer at long context with heavy hitters and local structure."""
+def profiled_traffic():
+    """`traffic_bytes_per_launch = N` from the committed counter summary, or None."""
+    try:
+        m = re.search(r"^traffic_bytes_per_launch\s*=\s*(\d+)", open(os.path.join(ROOT, TRAFFIC_PROFILE)).read(), re.M)
+        return int(m.group(1)) if m else None
+    except OSError:
+        return None
 
-    def __init__(self, config_no, n, tau, hq=32, hk=8, d_h=256, act=1):
+
+class Workload:
+    """One layer of one of the baseline's five configurations, resident on the GPU."""
+
+    def __init__(self, config_no, n=None, tau=0.9, hq=32, hk=8, d_h=256, act=1, structure=None, white=False):
+        if config_no == 1:
+            hq = hk = 1
+        n = n or DEFAULT_N[config_no]
         self.config_no, self.n, self.tau, self.hq, self.hk = config_no, n, tau, hq, hk
         self.theta = 1e6 if config_no != 5 else 5e5
+        self.structure = structure or ("plain" if config_no == 3 else "planted")
+        self.white = white
+        self.has_indexer = config_no >= 3
+        self.has_select = config_no >= 2
         seed = synth.config_seed(config_no)
         t0 = time.time()
-        q, k, v = synth.qkv(seed, hq, hk, n, local_structure=True)
+        q, k, v = synth.qkv(seed, hq, hk, n, local_structure=config_no >= 4)
         log("[bench] generated Q/K/V on the host in %.1fs" % (time.time() - t0))
         self.q, self.k, self.v = q.cuda(), k.cuda(), v.cuda()
         del q, k, v
         vs.rope_apply(self.q, 0, self.theta)
         vs.rope_apply(self.k, 0, self.theta)
-        u, cols = synth.heavy_hitter_plan(seed, hk, n)
-        self.q, self.k = synth.plant_heavy_hitters(self.q, self.k, u, cols)
-        W = synth.indexer_weights(seed, d_h, act)
-        self.W_host = W
-        d_s, d_v = synth.score_structure_profile(seed, hk, n, cols)
-        self.k, self.v = synth.plant_score_structure(self.k, self.v, W[0], W[2], W[3], d_s, d_v)
-        self.weights = vs.IndexerWeights(*[torch.from_numpy(x).cuda() for x in W], 0.0, 0.0, act)
-        self.cap = min(n, max(4096, n // 4))
-        self.budget = vs.Budget(mode=0, tau_v=tau, tau_s=tau, n_sink=min(4, n), n_local=min(64, n), cap_v=self.cap, cap_s=self.cap)
         dev = "cuda"
-        self.a_v = torch.empty((hk, n), dtype=torch.float32, device=dev)
-        self.a_s = torch.empty_like(self.a_v)
-        self.idx_v = torch.zeros((hk, self.cap), dtype=torch.int32, device=dev)
-        self.idx_s = torch.zeros_like(self.idx_v)
-        self.cnt_v = torch.zeros(hk, dtype=torch.int32, device=dev)
-        self.cnt_s = torch.zeros_like(self.cnt_v)
+        cols = None
+        if config_no in (2, 4, 5):
+            u, cols = synth.heavy_hitter_plan(seed, hk, n)
+            self.q, self.k = synth.plant_heavy_hitters(self.q, self.k, u, cols)
+        if self.has_indexer:
+            W = synth.indexer_weights(seed, d_h, act)
+            self.W_host = W
+            if self.structure == "planted":
+                d_s, d_v = synth.score_structure_profile(seed, hk, n, cols)
+                self.k, self.v = synth.plant_score_structure(self.k, self.v, W[0], W[2], W[3], d_s, d_v)
+            self.weights = vs.IndexerWeights(*[torch.from_numpy(x).cuda() for x in W], 0.0, 0.0, act)
+            self.ws_idx = torch.empty(max(1, vs.index_score_workspace(hk, n, d_h)), dtype=torch.uint8, device=dev)
+        if config_no == 1:
+            iv, cv, is_, cs = synth.fixed_lists(seed, n)
+            self.idx_v, self.cnt_v, self.idx_s, self.cnt_s = [torch.from_numpy(x).cuda() for x in (iv, cv, is_, cs)]
+            self.cap = iv.shape[1]
+        elif config_no == 2:
+            a_v, a_s = synth.structured_scores(seed, hk, n, white=white)
+            self.a_v, self.a_s = torch.from_numpy(a_v).cuda(), torch.from_numpy(a_s).cuda()
+            self.budget = vs.Budget(mode=1, k_v=1024, k_s=2048, n_sink=4, n_local=64, cap_v=1024 + 4, cap_s=2048 + 64)
+        else:
+            self.cap = min(n, max(4096, n // 4))
+            self.budget = vs.Budget(mode=0, tau_v=tau, tau_s=tau, n_sink=min(4, n), n_local=min(64, n), cap_v=self.cap,
+                                    cap_s=self.cap)
+            self.a_v = torch.empty((hk, n), dtype=torch.float32, device=dev)
+            self.a_s = torch.empty_like(self.a_v)
+        if self.has_select:
+            self.idx_v = torch.zeros((hk, self.budget.cap_v), dtype=torch.int32, device=dev)
+            self.idx_s = torch.zeros((hk, self.budget.cap_s), dtype=torch.int32, device=dev)
+            self.cnt_v = torch.zeros(hk, dtype=torch.int32, device=dev)
+            self.cnt_s = torch.zeros_like(self.cnt_v)
+            nsel = vs.select_budget_workspace(hk, n)
+            self.ws_sel = torch.empty(nsel, dtype=torch.uint8, device=dev) if nsel else None
         self.status = torch.zeros(hk, dtype=torch.int32, device=dev)
         self.o = torch.empty_like(self.q)
-        self.ws_idx = torch.empty(max(1, vs.index_score_workspace(hk, n, d_h)), dtype=torch.uint8, device=dev)
-        nsel = vs.select_budget_workspace(hk, n)
-        self.ws_sel = torch.empty(nsel, dtype=torch.uint8, device=dev) if nsel else None
         self.ws_att = torch.empty(vs.sparse_prefill_workspace(hq, hk, hk, n), dtype=torch.uint8, device=dev)
         torch.cuda.synchronize()
+
+    def describe(self):
+        heads = "%d q heads / %d KV heads, head_dim 128" % (self.hq, self.hk)
+        c = self.config_no
+        if c == 1:
+            return "C1: one head, n=%d, RoPE theta=1e6, fixed lists (4+60 columns, 64+64 offsets) -> fused sparse attention" % self.n
+        if c == 2:
+            return ("C2: one GQA layer (%s), n=%d, RoPE theta=1e6, 16 planted heavy hitters per KV head, fixed budget 1024 columns + "
+                    "2048 offsets by vs_select_budget from seeded %s scores -> fused sparse attention"
+                    % (heads, self.n, "UNSTRUCTURED (white-noise)" if self.white else "structured"))
+        tail = "VSIndexer(d_h=256, GELU) -> tau=%.2f budget (4 sinks, 64 local) -> fused sparse attention" % self.tau
+        if c == 3:
+            return ("C3: one 4B-shaped GQA layer (%s), n=%d, RoPE theta=1e6, N(0,1) tensors%s, %s"
+                    % (heads, self.n, "" if self.structure == "plain" else " + planted score bands", tail))
+        return ("C%d: one %s-shaped GQA layer (%s), n=%d, RoPE theta=%g, heavy hitters + local structure%s, %s"
+                % (c, "4B" if c == 4 else "8B", heads, self.n, self.theta,
+                   " + planted score bands" if self.structure == "planted" else " (no planted score bands)", tail))
 
     def indexer(self):
         vs.index_score(self.k, self.v, self.weights, self.a_v, self.a_s, self.ws_idx)
@@ -87,8 +149,10 @@ class Workload:
         vs.sparse_prefill(self.q, self.k, self.v, self.idx_v, self.cnt_v, self.idx_s, self.cnt_s, self.o, None, self.ws_att)
 
     def step(self):
-        self.indexer()
-        self.select()
+        if self.has_indexer:
+            self.indexer()
+        if self.has_select:
+            self.select()
         self.attention()
 
     def dense(self):
@@ -122,37 +186,41 @@ def live_pairs(idx_v, cnt_v, idx_s, cnt_s, n, group):
 def cpu_baseline(w, idx_v, cnt_v, idx_s, cnt_s, pairs_total, dense_flop):
     """The fp64 oracle, as it stands, timed on this host on a bounded sample of the same workload (about 15 s): the
     indexer on half of the KV heads, the selection on every head and direction, attention on a declared row sample of
-    one KV group (scaled by live pairs)."""
+    one KV group (scaled by live pairs).  Stages a configuration does not have are left out."""
     import oracle
     n = w.n
     threads = min(16, os.cpu_count() or 1)
     hs = max(1, w.hk // 2)
     kb, vb = synth.to_bits(w.k[:hs]), synth.to_bits(w.v[:hs])
-    t0 = time.time()
-    oracle.index_score(kb, vb, *w.W_host, act=1, threads=threads)
-    t_idx_sample = time.time() - t0
-    t_idx = t_idx_sample * w.hk / hs
-    a_v, a_s = w.a_v.cpu().numpy(), w.a_s.cpu().numpy()
-    t0 = time.time()
-    for a, forced in ((a_v, 4), (a_s, 64)):
-        for g in range(w.hk):
-            oracle.select(a[g:g + 1], 0, w.tau, 0, forced, w.cap)
-    t_sel = time.time() - t0
+    parts, stages = [], {}
+    if w.has_indexer:
+        t0 = time.time()
+        oracle.index_score(kb, vb, *w.W_host, act=1, threads=threads)
+        t_idx_sample = time.time() - t0
+        stages["indexer"] = t_idx_sample * w.hk / hs
+        parts.append("indexer: %d KV heads x %d tokens, %.1fs (scaled to %d heads)" % (hs, n, t_idx_sample, w.hk))
+    if w.has_select:
+        a_v, a_s = w.a_v.cpu().numpy(), w.a_s.cpu().numpy()
+        b = w.budget
+        t0 = time.time()
+        for a, forced, tau, kfix, cap in ((a_v, b.n_sink, b.tau_v, b.k_v, b.cap_v), (a_s, max(b.n_local, 1), b.tau_s, b.k_s, b.cap_s)):
+            for g in range(w.hk):
+                oracle.select(a[g:g + 1], b.mode, tau, kfix, forced, cap)
+        stages["select"] = time.time() - t0
+        parts.append("select: all %d heads x 2 directions, %.2fs, one thread" % (w.hk, stages["select"]))
     group = w.hq // w.hk
     qb = synth.to_bits(w.q[:group])
-    rows = synth.sample_rows(1, n, 2048, 2048, 36000)
+    rows = synth.sample_rows(1, n, min(2048, n), min(2048, n), min(36000, n))
     t0 = time.time()
     _, _, live = oracle.sparse_attention(qb, kb[:1], vb[:1], idx_v[:1], cnt_v[:1], idx_s[:1], cnt_s[:1], rows=rows,
                                          threads=threads, return_live=True)
     t_att_sample = time.time() - t0
-    t_att = t_att_sample * pairs_total / max(1, int(live.sum()))
-    total = t_idx + t_sel + t_att
+    stages["attention"] = t_att_sample * pairs_total / max(1, int(live.sum()))
+    parts.append("attention: %d sampled rows x %d query heads of KV group 0, %.1fs, extrapolated by live pairs"
+                 % (len(rows), group, t_att_sample))
+    total = sum(stages.values())
     return {"value": dense_flop / total / 1e12, "unit": "TFLOP/s (dense-equivalent)", "cores": threads, "kind": "oracle",
-            "sample": "indexer: %d KV heads x %d tokens, %.1fs (scaled to %d heads); select: all %d heads x 2 directions, "
-                      "%.2fs, one thread; attention: %d sampled rows x %d query heads of KV group 0, %.1fs, extrapolated by "
-                      "live pairs" % (hs, n, t_idx_sample, w.hk, w.hk, t_sel, len(rows), group, t_att_sample),
-            "seconds_per_layer_extrapolated": total,
-            "seconds_by_stage_extrapolated": {"indexer": t_idx, "select": t_sel, "attention": t_att}}
+            "sample": "; ".join(parts), "seconds_per_layer_extrapolated": total, "seconds_by_stage_extrapolated": stages}
 
 
 def sweep(w, args, t_dense, dense_flop, dense_tiles, causal_pairs):
@@ -217,18 +285,50 @@ def sweep(w, args, t_dense, dense_flop, dense_tiles, causal_pairs):
     return res
 
 
+def stage_report(w, t_idx, t_sel, t_att, tiles, staged_gather, staged_block, d_h=256):
+    """Every stage against the roofline that bounds it (algorithmic bytes and flops; all derived in the design doc)."""
+    n, hk = w.n, w.hk
+    stages = {}
+    if w.has_indexer:
+        by = hk * n * (512 + 8)                              # K and V rows read once, two scores written
+        fl = hk * n * 2.0 * 2 * 256 * d_h                    # two bf16 passes (hi + lo) of the [n, 256] x [256, d_h] contraction
+        gbs, tf = by / (t_idx * 1e-3) / 1e9, fl / (t_idx * 1e-3) / 1e12
+        stages["indexer"] = {"ms": t_idx, "bytes": by, "GB/s": gbs, "frac_hbm": gbs / PEAK_HBM_GBS, "mfma_TFLOP/s": tf,
+                             "frac_mfma": tf / PEAK_BF16_TFLOPS,
+                             "bound": "mfma (split contraction) + activation VALU; the HBM floor is %.0f us" % (by / PEAK_HBM_GBS / 1e3)}
+    if w.has_select:
+        by = 2 * hk * n * 4 + 4 * int(w.cnt_v.sum().item() + w.cnt_s.sum().item())   # every score once, the lists once
+        gbs = by / (t_sel * 1e-3) / 1e9
+        stages["select"] = {"ms": t_sel, "bytes": by, "GB/s": gbs, "frac_hbm": gbs / PEAK_HBM_GBS,
+                            "bound": "latency / L2 (scores are re-read from L2 by the radix passes)"}
+    fl = tiles * FLOP_PER_TILE
+    gby = staged_gather * STAGED_TILE_BYTES
+    bby = staged_block * STAGED_TILE_BYTES
+    stages["attention"] = {"ms": t_att, "executed_tiles": tiles, "TFLOP/s": fl / (t_att * 1e-3) / 1e12,
+                           "frac_mfma": fl / (t_att * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, "bound": "mfma"}
+    stages["gathers"] = {"staged_gather_tiles": staged_gather, "bytes": gby, "GB/s_over_kernel": gby / (t_att * 1e-3) / 1e9,
+                         "frac_hbm": gby / (t_att * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                         "staged_block_tiles": staged_block, "block_bytes": bby,
+                         "note": "row gathers of selected columns into LDS (256-byte rows of K and of V), counted by the kernel; "
+                                 "most of them are served by the L2 of the head's XCD"}
+    return stages
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--n", type=int, default=131072)
+    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--n", type=int, default=None, help="sequence length (default: the configuration's own)")
     ap.add_argument("--tau", type=float, default=0.9)
-    ap.add_argument("--config", type=int, default=4, choices=[4, 5])
+    ap.add_argument("--structure", choices=["planted", "plain"], default=None,
+                    help="configs 3-5: plant score bands along the indexer's sensitive directions or not (default: plain for 3, planted for 4 and 5)")
+    ap.add_argument("--white", action="store_true", help="config 2: unstructured (white-noise) score vectors")
     ap.add_argument("--dense-reps", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true",
-                    help="also time tau in {0.85, 0.9, 0.95}, the tile-granular slash mode, the paper-shaped indexer (SiLU, 1024), "
+                    help="configs 4 / 5: also time tau in {0.85, 0.9, 0.95}, the tile-granular slash mode, the paper-shaped indexer (SiLU, 1024), "
                          "the aggregation of the dense attention map with the recall of the selection, "
                          "and a 36-layer pass with a seeded tau per layer in [0.8, 0.95] (same tensors for every layer)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -242,7 +342,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
-    w = Workload(args.config, args.n, args.tau)
+    w = Workload(args.config, args.n, args.tau, structure=args.structure, white=args.white)
     n, hq = w.n, w.hq
 
     for _ in range(args.warmup):
@@ -256,11 +356,11 @@ def main():
 
     # per-stage split and the dominant kernel's own duration (same launch configuration)
     reps = max(3, min(args.steps, 10))
-    t_idx = float(np.median(timed(w.indexer, reps)))
-    t_sel = float(np.median(timed(w.select, reps)))
+    t_idx = float(np.median(timed(w.indexer, reps))) if w.has_indexer else 0.0
+    t_sel = float(np.median(timed(w.select, reps))) if w.has_select else 0.0
     att = timed(w.attention, reps)
     t_att = float(np.mean(att))
-    tiles = vs.sparse_prefill_tiles(w.ws_att)
+    tiles, staged_gather, staged_block = vs.sparse_prefill_counters(w.ws_att)
     w.dense()
     torch.cuda.synchronize()
     t_dense = float(np.median(timed(w.dense, args.dense_reps)))
@@ -279,10 +379,12 @@ def main():
     pairs = live_pairs(idx_v, cnt_v, idx_s, cnt_s, n, hq // w.hk)
     causal_pairs = hq * n * (n + 1) // 2
     dense_flop = hq * 2.0 * n * n * 128
-    dense_tiles = hq * (n // 32) * (n // 32 + 1) // 2
+    dense_tiles = hq * ((n + 31) // 32) * ((n + 31) // 32 + 1) // 2
 
     exec_flop = tiles * FLOP_PER_TILE
     achieved = exec_flop / (t_att * 1e-3) / 1e12
+    default_point = args.config == 4 and n == 131072 and args.tau == 0.9 and w.structure == "planted"
+    traffic = profiled_traffic() if default_point else None
     out = {
         "metric": "sparse_prefill_effective_tflops_128k" if n == 131072 else "sparse_prefill_effective_tflops",
         "value": dense_flop / (ms_step * 1e-3) / 1e12,
@@ -291,27 +393,29 @@ def main():
         "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "C%d: one 4B-shaped GQA layer (32 q heads / 8 KV heads, head_dim 128), n=%d, RoPE theta=%g, "
-                               "heavy hitters + local structure + planted score bands, VSIndexer(d_h=256, GELU) -> tau=%.2f budget (4 sinks, 64 local) -> "
-                               "fused sparse attention" % (args.config, n, w.theta, args.tau),
-                   "seq_len": n, "q_heads": hq, "kv_heads": w.hk, "tau": args.tau},
+        "config": {"workload": w.describe(), "seq_len": n, "q_heads": hq, "kv_heads": w.hk, "tau": args.tau if w.config_no >= 3 else None},
         "ms_per_layer": {"indexer": t_idx, "select": t_sel, "sparse_attention": t_att, "step": ms_step,
                          "step_wall_clock": wall_ms, "dense_causal": t_dense},
         "speedup_vs_dense": t_dense / ms_step,
         "dense_tflops": dense_flop / (t_dense * 1e-3) / 1e12,
+        "dense_frac_mfma": dense_flop / (t_dense * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "budget": {"k_v": cnt_v.tolist(), "k_s": cnt_s.tolist(), "status": status.tolist(),
                    "budget_fraction": pairs / causal_pairs, "tile_coverage": tiles / dense_tiles,
                    "tile_efficiency": pairs / (tiles * 1024.0)},
+        "stages": stage_report(w, t_idx, t_sel, t_att, tiles, staged_gather, staged_block),
         "paper_context": "paper reports 4.95x (8.42x aggressive) over FlashAttention at 128k on unstated NVIDIA hardware",
         "roofline": {"kernel": "vs_attention_kernel", "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES if (args.config == 4 and n == 131072 and args.tau == 0.9) else None,
+                     "traffic": traffic, "traffic_source": TRAFFIC_PROFILE if traffic is not None else None,
                      "flop_per_launch": exec_flop, "avg_launch_ms": t_att, "executed_tiles": tiles},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, idx_v, cnt_v, idx_s, cnt_s, pairs, dense_flop)
     if args.sweep:
-        out["sweep"] = sweep(w, args, t_dense, dense_flop, dense_tiles, causal_pairs)
+        if args.config < 4:
+            log("[bench] --sweep applies to configs 4 and 5 only: skipped")
+        else:
+            out["sweep"] = sweep(w, args, t_dense, dense_flop, dense_tiles, causal_pairs)
     print(json.dumps(out))
 
 

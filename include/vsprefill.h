@@ -250,6 +250,14 @@ int vs_aggregate(const void* q, const void* k, int q_heads, int kv_heads, int64_
  */
 int vs_sparse_prefill_tiles(const void* ws, size_t ws_bytes, void* stream, int64_t* executed_tiles_host);
 
+/*
+ * The three counters of the last vs_sparse_prefill that used this workspace, copied to the HOST array counters_host[3]
+ * after synchronising `stream`: [0] executed MFMA tiles (as vs_sparse_prefill_tiles), [1] 32-key tiles staged in LDS by
+ * row gathers of selected columns (each is 32 rows of K and of V, 256 bytes per row: 16 KiB), [2] 32-key tiles staged
+ * as contiguous key blocks of the slash part.
+ */
+int vs_sparse_prefill_counters(const void* ws, size_t ws_bytes, void* stream, int64_t* counters_host);
+
 const char* vs_strerror(int status);
 int vs_last_hip_error(void);
 const char* vs_version(void);

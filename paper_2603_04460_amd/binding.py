@@ -14,7 +14,7 @@ EXPORTS = [
     "vs_rope_apply", "vs_index_score_workspace", "vs_index_score", "vs_select_budget_workspace", "vs_select_budget",
     "vs_sparse_prefill_workspace", "vs_sparse_prefill", "vs_sparse_prefill_tiled", "vs_sparse_prefill_chunk",
     "vs_sparse_prefill_static", "vs_dense_prefill", "vs_dense_prefill_chunk", "vs_validate_lists",
-    "vs_sparse_prefill_tiles", "vs_aggregate_workspace", "vs_aggregate",
+    "vs_sparse_prefill_tiles", "vs_sparse_prefill_counters", "vs_aggregate_workspace", "vs_aggregate",
     "vs_strerror", "vs_last_hip_error", "vs_version",
 ]
 
@@ -71,6 +71,7 @@ def _load():
     L.vs_dense_prefill_chunk.argtypes = [vp, vp, vp, i32, i32, i64, i64, i64, f32, vp, vp, vp]
     L.vs_validate_lists.argtypes = [vp, vp, i32, i32, i64, vp, vp]
     L.vs_sparse_prefill_tiles.argtypes = [vp, sz, vp, ctypes.POINTER(ctypes.c_int64)]
+    L.vs_sparse_prefill_counters.argtypes = [vp, sz, vp, ctypes.POINTER(ctypes.c_int64)]
     L.vs_aggregate_workspace.argtypes = [i32, i32, i32, i64]
     L.vs_aggregate_workspace.restype = sz
     L.vs_aggregate.argtypes = [vp, vp, i32, i32, i64, f32, vp, i32, vp, vp, vp, vp, i32, vp, vp, i32, i32, vp, vp, sz, vp]
@@ -283,6 +284,14 @@ def sparse_prefill_tiles(ws, stream=None):
     _check(_load().vs_sparse_prefill_tiles(_ptr(ws), ws.numel() * ws.element_size(), _stream(stream), ctypes.byref(out)),
            "vs_sparse_prefill_tiles")
     return out.value
+
+
+def sparse_prefill_counters(ws, stream=None):
+    """(executed MFMA tiles, staged gather tiles, staged block tiles) of the last sparse call on this workspace."""
+    out = (ctypes.c_int64 * 3)()
+    _check(_load().vs_sparse_prefill_counters(_ptr(ws), ws.numel() * ws.element_size(), _stream(stream), out),
+           "vs_sparse_prefill_counters")
+    return int(out[0]), int(out[1]), int(out[2])
 
 
 def aggregate_workspace(q_heads, kv_heads, index_heads, n):

@@ -170,7 +170,7 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
     for (int db = 0; db < 4; ++db)
 #pragma unroll
         for (int e = 0; e < 16; ++e) oacc[db][e] = 0.f;
-    unsigned int tiles_done = 0;
+    unsigned int tiles_done = 0, staged_gather = 0, staged_block = 0;
 
     // ---- staging: a stage is two 32-key tiles; a thread moves one 16-byte chunk of rows st_row and st_row + 16 of K and V of each ----
     const int st_row = tid >> 4;
@@ -343,6 +343,8 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
         constexpr bool GATHER = decltype(gather_tag)::value;
         if (ntiles == 0) return;
         const int nstages = (ntiles + 1) >> 1;
+        if (GATHER) staged_gather += static_cast<unsigned int>(ntiles);   // 32-key tiles this workgroup stages in LDS
+        else staged_block += static_cast<unsigned int>(ntiles);
         auto stage_rows = [&](int st, int (&rows)[2][2]) __attribute__((always_inline)) {
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
@@ -562,6 +564,10 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
             p.lse[static_cast<size_t>(my_head) * p.nq + (row - p.pos0)] = l_tot > 0.f ? m_run * p.scale + __logf(l_tot) : NEG_INF;
     }
     if (p.tile_counter && lane == 0 && tiles_done) atomicAdd(p.tile_counter, static_cast<unsigned long long>(tiles_done));
+    if (p.tile_counter && tid == 0) {
+        if (staged_gather) atomicAdd(p.tile_counter + 1, static_cast<unsigned long long>(staged_gather));
+        if (staged_block) atomicAdd(p.tile_counter + 2, static_cast<unsigned long long>(staged_block));
+    }
     if (!p.work_counter) break;
     }
 }
@@ -690,7 +696,7 @@ SparseWs sparse_ws_layout(int kv_heads, int index_heads, int64_t n) {
     w.vw = static_cast<int>(vs::round_up(static_cast<size_t>(nblk + 4), 4));
     w.nq32 = static_cast<int>(nblk);
     w.dcap = static_cast<int>(nblk + 4);
-    w.counter_off = 0;                                      // 8 bytes of tile counter, then from byte 64 one counter per KV head
+    w.counter_off = 0;                                      // three 8-byte tile counters, then from byte 64 one counter per KV head
     w.sbit_off = vs::round_up(64 + static_cast<size_t>(kv_heads) * 4, 256);
     w.vbit_off = w.sbit_off + ih * w.sw * 4;
     w.ncol_off = vs::round_up(w.vbit_off + ih * w.vw * 4, 256);
@@ -891,12 +897,20 @@ int vs_sparse_prefill_static(const void* q, const void* k, const void* v, int q_
 }
 
 int vs_sparse_prefill_tiles(const void* ws, size_t ws_bytes, void* stream, int64_t* executed_tiles_host) {
-    if (!ws || ws_bytes < 256 || !executed_tiles_host) return VS_ERR_INVALID_ARG;
+    if (!executed_tiles_host) return VS_ERR_INVALID_ARG;
+    int64_t c[3] = {0, 0, 0};
+    const int rc = vs_sparse_prefill_counters(ws, ws_bytes, stream, c);
+    if (rc == VS_OK) *executed_tiles_host = c[0];
+    return rc;
+}
+
+int vs_sparse_prefill_counters(const void* ws, size_t ws_bytes, void* stream, int64_t* counters_host) {
+    if (!ws || ws_bytes < 256 || !counters_host) return VS_ERR_INVALID_ARG;
     hipStream_t st = static_cast<hipStream_t>(stream);
     VS_HIP(hipStreamSynchronize(st));
-    unsigned long long c = 0;
-    VS_HIP(hipMemcpy(&c, ws, sizeof(c), hipMemcpyDeviceToHost));
-    *executed_tiles_host = static_cast<int64_t>(c);
+    unsigned long long c[3] = {0, 0, 0};
+    VS_HIP(hipMemcpy(c, ws, sizeof(c), hipMemcpyDeviceToHost));
+    for (int i = 0; i < 3; ++i) counters_host[i] = static_cast<int64_t>(c[i]);
     return VS_OK;
 }
 

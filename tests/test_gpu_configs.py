@@ -54,53 +54,37 @@ def _check_attention(w, lists, rows):
     return check_attention(w.o, lse, ref_o, ref_lse, rows=rows)
 
 
-def test_config2_fixed_budget_32k():
+@pytest.mark.parametrize("white", [False, True])
+def test_config2_fixed_budget_32k(white):
     """32 / 8 heads, n = 32768, planted heavy hitters, fixed budget 1024 columns + 2048 offsets per KV head chosen
-    by vs_select_budget from seeded structured scores."""
-    n, hq, hk = 32768, 32, 8
-    seed = synth.config_seed(2)
-    q, k, v = synth.qkv(seed, hq, hk, n)
-    q, k, v = q.cuda(), k.cuda(), v.cuda()
-    vs.rope_apply(q, 0, 1e6)
-    vs.rope_apply(k, 0, 1e6)
-    u, cols = synth.heavy_hitter_plan(seed, hk, n)
-    q, k = synth.plant_heavy_hitters(q, k, u, cols)
-    a_v, a_s = synth.structured_scores(seed, hk, n)
-    budget = vs.Budget(mode=1, k_v=1024, k_s=2048, n_sink=4, n_local=64, cap_v=1024 + 4, cap_s=2048 + 64)
-    av, as_ = torch.from_numpy(a_v).cuda(), torch.from_numpy(a_s).cuda()
-    idx_v = torch.zeros((hk, budget.cap_v), dtype=torch.int32, device="cuda")
-    idx_s = torch.zeros((hk, budget.cap_s), dtype=torch.int32, device="cuda")
-    cnt_v = torch.zeros(hk, dtype=torch.int32, device="cuda")
-    cnt_s = torch.zeros_like(cnt_v)
-    status = torch.zeros_like(cnt_v)
-    vs.select_budget(av, as_, budget, idx_v, cnt_v, idx_s, cnt_s, status, None)
-    rv = oracle.select(a_v, 1, 0.0, 1024, 4, budget.cap_v)
-    rs = oracle.select(a_s, 1, 0.0, 2048, 64, budget.cap_s)
-    iv, cv, is_, cs = idx_v.cpu().numpy(), cnt_v.cpu().numpy(), idx_s.cpu().numpy(), cnt_s.cpu().numpy()
-    np.testing.assert_array_equal(cv, rv[1])
-    np.testing.assert_array_equal(cs, rs[1])
-    for h in range(hk):
-        np.testing.assert_array_equal(iv[h, :cv[h]], rv[0][h, :cv[h]])
-        np.testing.assert_array_equal(is_[h, :cs[h]], rs[0][h, :cs[h]])
-    o = torch.empty_like(q)
+    by vs_select_budget from seeded score vectors: structured, and unstructured (white noise: scattered offsets touch
+    almost every key block, the worst case for the fused kernel)."""
+    w = bench.Workload(2, white=white)
+    n, hq, hk = w.n, w.hq, w.hk
+    w.select()
+    torch.cuda.synchronize()
+    lists = _check_selection(w)
+    iv, cv, is_, cs = lists
+    assert (cv >= 1024).all() and (cv <= 1024 + 4).all() and (cs >= 2048).all() and (cs <= 2048 + 64).all()
     lse = torch.empty((hq, n), dtype=torch.float32, device="cuda")
-    ws = torch.empty(vs.sparse_prefill_workspace(hq, hk, hk, n), dtype=torch.uint8, device="cuda")
-    vs.sparse_prefill(q, k, v, idx_v, cnt_v, idx_s, cnt_s, o, lse, ws)
-    tiles = vs.sparse_prefill_tiles(ws)
-    rows = synth.sample_rows(seed, n, 32, 32, 64)
-    ref_o, ref_lse, live = oracle.sparse_attention(synth.to_bits(q), synth.to_bits(k), synth.to_bits(v), iv, cv, is_, cs,
+    vs.sparse_prefill(w.q, w.k, w.v, w.idx_v, w.cnt_v, w.idx_s, w.cnt_s, w.o, lse, w.ws_att)
+    tiles = vs.sparse_prefill_tiles(w.ws_att)
+    rows = synth.sample_rows(synth.config_seed(2), n, 32, 32, 64)
+    ref_o, ref_lse, live = oracle.sparse_attention(synth.to_bits(w.q), synth.to_bits(w.k), synth.to_bits(w.v), iv, cv, is_, cs,
                                                    rows=rows, return_live=True)
-    check_attention(o, lse, ref_o, ref_lse, rows=rows)
+    check_attention(w.o, lse, ref_o, ref_lse, rows=rows)
     assert tiles * 1024 >= bench.live_pairs(iv, cv, is_, cs, n, hq // hk)
-    check_key_set(k, iv, cv, is_, cs, hq, rows)
-    # the planted heavy hitters really dominate their rows: the selected set contains them when scores say so
     assert live.min() >= 1
+    check_key_set(w.k, iv, cv, is_, cs, hq, rows)
 
 
-@pytest.mark.parametrize("config,n,taus", [(3, 65536, (0.9,)), (4, 131072, (0.85, 0.95, 0.9)), (5, 131072, (0.9,))])
-def test_pipeline_configs(config, n, taus):
-    """Configs 3 - 5: indexer -> cumulative-threshold budget -> sparse attention on one 32 / 8-head layer."""
-    w = bench.Workload(4 if config == 3 else config, n, taus[-1])
+@pytest.mark.parametrize("config,taus,structure", [(3, (0.9,), None), (4, (0.85, 0.95, 0.9), None), (4, (0.9,), "plain"),
+                                                   (5, (0.9,), None)])
+def test_pipeline_configs(config, taus, structure):
+    """Configs 3 - 5: indexer -> cumulative-threshold budget -> sparse attention on one 32 / 8-head layer, at the sizes and
+    in the launch configuration bench.py times; config 4 also without the planted score bands."""
+    w = bench.Workload(config, None, taus[-1], structure=structure)
+    n = w.n
     w.indexer()
     torch.cuda.synchronize()
     _check_scores(w)
