@@ -5,5 +5,5 @@ may import this package.  It shares no code with the GPU library.
 """
 from .vs_oracle import (  # noqa: F401
     build, rope_f64, rope_bf16, index_score, select, sparse_attention, dense_attention,
-    vs_aggregate, f64_to_bf16, bf16_to_f64,
+    vs_aggregate, f64_to_bf16, bf16_to_f64, index_train, TRAIN_EPS,
 )

@@ -18,6 +18,9 @@
 //                         Eqs. P, A, O) under the causal mask
 //   vso_vs_aggregate      column and diagonal sums of the causal attention matrix
 //                         (Sec. "Obtaining Ground Truth") and vso_recall (Eq. R(S))
+//   vso_index_train       distillation loss L = KL(A^_v || A_v) + KL(A^_s || A_s) (Sec. "Vertical-Slash
+//                         Aggregation for Distillation Training", paragraph "Loss function design") and
+//                         its gradient with respect to the indexer's parameters, by the chain rule
 //
 // Parity pins live in tests/ (brute force on tiny inputs, closed forms, hand-worked masks,
 // library special cases).  No function here is "parity unpinned".
@@ -407,6 +410,82 @@ int vso_vs_aggregate(const uint16_t* q, const uint16_t* k, int64_t n, int d, dou
     }
     for (int64_t j = 0; j < n; ++j) { a_v[j] /= n; a_s[j] /= n; }
     if (recall) *recall /= n;
+    return 0;
+}
+
+// Distillation loss of the VSIndexer and its gradient (paragraph "Loss function design").
+// Forward as vso_index_score: A^_d = softmax over the n positions of the logits of direction d, per KV head.
+// Loss, as the paper prints it (prediction first):  KL(A^ || A) = sum_t A^_t (ln A^_t - ln max(A_t, eps)),
+//   L = (1 / kv_heads) * sum over heads of [ KL(A^_v || A_v) + KL(A^_s || A_s) ].
+// eps floors the target (a target of exactly zero would make the term infinite).  Terms with A^_t = 0 contribute 0.
+// Gradient by the chain rule, every quantity in fp64:
+//   dL/dlogit_d[t] = A^_d[t] * ( (ln A^_d[t] - ln A_d[t]) - KL_d ) / kv_heads
+//   z = act(pre), pre = x W_U + b_U;  dz_u = g_v W_V[u] + g_s W_S[u];  dpre_u = dz_u act'(pre_u)
+//   dW_V[u] = sum_t g_v[t] z_u(t), dW_S likewise;  db_U[u] = sum_t dpre_u(t);  dW_U[c,u] = sum_t x_t[c] dpre_u(t)
+// (sums over the tokens of every head; the scalar output biases get zero gradient: they cancel in the softmax).
+// targets t_v, t_s: [kv_heads, n] fp64.  Outputs: loss (1), dW_U [2d, d_h], db_U, dW_V, dW_S [d_h] fp64;
+// glogit_v / glogit_s optional [kv_heads, n].
+int vso_index_train(const uint16_t* k, const uint16_t* v, int kv_heads, int64_t n, int d,
+                    const float* W_U, const float* b_U, const float* W_V, const float* W_S, float b_V, float b_S,
+                    int d_h, int act, const double* t_v, const double* t_s, double eps,
+                    double* loss, double* dW_U, double* db_U, double* dW_V, double* dW_S,
+                    double* glogit_v, double* glogit_s) {
+    if (!k || !v || !W_U || !b_U || !W_V || !W_S || !t_v || !t_s || !loss || !dW_U || !db_U || !dW_V || !dW_S) return -1;
+    if (kv_heads <= 0 || n <= 0 || d <= 0 || d_h <= 0 || act < 0 || act > 1 || !(eps > 0.0)) return -1;
+    const int64_t rows = static_cast<int64_t>(kv_heads) * n;
+    std::vector<double> a_v(rows), a_s(rows);
+    int rc = vso_index_score(k, v, kv_heads, n, d, W_U, b_U, W_V, W_S, b_V, b_S, d_h, act, a_v.data(), a_s.data(), nullptr,
+                             nullptr, 1);
+    if (rc != 0) return rc;
+    std::vector<double> g_v(rows, 0.0), g_s(rows, 0.0);
+    double total = 0.0;
+    for (int h = 0; h < kv_heads; ++h)
+        for (int dir = 0; dir < 2; ++dir) {
+            const double* p = (dir == 0 ? a_v.data() : a_s.data()) + static_cast<int64_t>(h) * n;
+            const double* q = (dir == 0 ? t_v : t_s) + static_cast<int64_t>(h) * n;
+            double* g = (dir == 0 ? g_v.data() : g_s.data()) + static_cast<int64_t>(h) * n;
+            std::vector<double> diff(n, 0.0);
+            double kl = 0.0;
+            for (int64_t t = 0; t < n; ++t) {
+                if (p[t] > 0.0) {
+                    diff[t] = std::log(p[t]) - std::log(std::max(q[t], eps));
+                    kl += p[t] * diff[t];
+                }
+            }
+            for (int64_t t = 0; t < n; ++t) g[t] = p[t] * (diff[t] - kl) / kv_heads;
+            total += kl;
+        }
+    *loss = total / kv_heads;
+    for (int64_t i = 0; i < static_cast<int64_t>(2) * d * d_h; ++i) dW_U[i] = 0.0;
+    for (int u = 0; u < d_h; ++u) db_U[u] = dW_V[u] = dW_S[u] = 0.0;
+    std::vector<double> x(2 * d);
+    for (int64_t row = 0; row < rows; ++row) {
+        for (int c = 0; c < d; ++c) {
+            x[c] = bf16_to_f64(k[row * d + c]);
+            x[d + c] = bf16_to_f64(v[row * d + c]);
+        }
+        for (int u = 0; u < d_h; ++u) {
+            double pre = static_cast<double>(b_U[u]);
+            for (int c = 0; c < 2 * d; ++c) pre += x[c] * static_cast<double>(W_U[static_cast<int64_t>(c) * d_h + u]);
+            double z = activation(pre, act);
+            double slope;
+            if (act == 0) {                                   // SiLU: s + x s (1 - s), s = sigmoid(x)
+                double sg = 1.0 / (1.0 + std::exp(-pre));
+                slope = sg + pre * sg * (1.0 - sg);
+            } else {                                          // GELU: Phi(x) + x phi(x)
+                double Phi = 0.5 * (1.0 + std::erf(pre / std::sqrt(2.0)));
+                double phi = std::exp(-0.5 * pre * pre) / std::sqrt(2.0 * 3.14159265358979323846);
+                slope = Phi + pre * phi;
+            }
+            dW_V[u] += g_v[row] * z;
+            dW_S[u] += g_s[row] * z;
+            double dpre = (g_v[row] * static_cast<double>(W_V[u]) + g_s[row] * static_cast<double>(W_S[u])) * slope;
+            db_U[u] += dpre;
+            for (int c = 0; c < 2 * d; ++c) dW_U[static_cast<int64_t>(c) * d_h + u] += x[c] * dpre;
+        }
+    }
+    if (glogit_v) std::copy(g_v.begin(), g_v.end(), glogit_v);
+    if (glogit_s) std::copy(g_s.begin(), g_s.end(), glogit_s);
     return 0;
 }
 

@@ -184,3 +184,30 @@ def vs_aggregate(q, k, scale=None, idx_v=None, idx_s=None):
                             ctypes.byref(rec) if want else None)
     assert rc == 0, rc
     return (a_v, a_s, rec.value) if want else (a_v, a_s)
+
+
+TRAIN_EPS = 1e-30
+
+
+def index_train(k, v, W_U, b_U, W_V, W_S, t_v, t_s, b_V=0.0, b_S=0.0, act=1, eps=TRAIN_EPS, return_glogits=False):
+    """Distillation loss L = mean over heads of KL(A^_v || A_v) + KL(A^_s || A_s) and its gradient.
+    k, v: [kv_heads, n, d] uint16; targets t_v, t_s: [kv_heads, n].  Returns (loss, dW_U, db_U, dW_V, dW_S) in float64
+    (and the gradients with respect to the logits when asked)."""
+    L = _load()
+    k = _c(k, np.uint16); v = _c(v, np.uint16)
+    W_U = _c(W_U, np.float32); b_U = _c(b_U, np.float32); W_V = _c(W_V, np.float32); W_S = _c(W_S, np.float32)
+    t_v = _c(t_v, np.float64); t_s = _c(t_s, np.float64)
+    hk, n, d = k.shape
+    d_h = W_U.shape[1]
+    assert W_U.shape[0] == 2 * d and t_v.shape == (hk, n) and t_s.shape == (hk, n)
+    loss = ctypes.c_double(0.0)
+    dW_U = np.empty((2 * d, d_h)); db_U = np.empty(d_h); dW_V = np.empty(d_h); dW_S = np.empty(d_h)
+    g_v = np.empty((hk, n)) if return_glogits else None
+    g_s = np.empty((hk, n)) if return_glogits else None
+    rc = L.vso_index_train(_p(k), _p(v), ctypes.c_int(hk), ctypes.c_int64(n), ctypes.c_int(d), _p(W_U), _p(b_U), _p(W_V),
+                           _p(W_S), ctypes.c_float(b_V), ctypes.c_float(b_S), ctypes.c_int(d_h), ctypes.c_int(act),
+                           _p(t_v), _p(t_s), ctypes.c_double(eps), ctypes.byref(loss), _p(dW_U), _p(db_U), _p(dW_V), _p(dW_S),
+                           _p(g_v), _p(g_s))
+    assert rc == 0, rc
+    out = (loss.value, dW_U, db_U, dW_V, dW_S)
+    return out + (g_v, g_s) if return_glogits else out
