@@ -242,6 +242,27 @@ int vs_aggregate(const void* q, const void* k, int q_heads, int kv_heads, int64_
                  const int32_t* idx_s, const int32_t* cnt_s, int cap_s, int index_heads, float* recall, void* ws,
                  size_t ws_bytes, void* stream);
 
+size_t vs_index_train_workspace(int kv_heads, int64_t n, int d_h);
+
+/*
+ * One distillation step of the VSIndexer without the optimizer (Sec. "Vertical-Slash Aggregation for Distillation
+ * Training", paragraph "Loss function design"): forward as vs_index_score, then
+ *     L = (1 / kv_heads) * sum over heads of [ KL(A^_v || A_v) + KL(A^_s || A_s) ],
+ *     KL(P || Q) = sum_t P_t (ln P_t - ln max(Q_t, eps))            (prediction first, as the paper prints it)
+ * and the gradient of L with respect to W_U, b_U, W_V, W_S (the scalar output biases cancel in the softmax: their
+ * gradient is zero).  Only the indexer is differentiated; K, V and the targets are constants (frozen backbone).
+ *   k, v        [kv_heads, n, 128] bf16 as for vs_index_score
+ *   t_v, t_s    [kv_heads, n] fp32 target distributions, e.g. vs_aggregate's a_v / a_s with out_heads = kv_heads
+ *   eps         floor of the targets inside the logarithm (> 0)
+ *   loss        [1] fp32 out (device);  dW_U [256, d_h], db_U, dW_V, dW_S [d_h] fp32 out (device, overwritten)
+ * Arithmetic: the inference kernels for the forward; fp64 sums for the loss; the hidden activations are recomputed on
+ * the matrix cores (W_U as two bf16 terms), pre-activation gradients enter the second contraction as two bf16 terms,
+ * fp32 accumulation per workgroup and a fixed-order fp64 reduction over workgroups: the step is deterministic.
+ */
+int vs_index_train_step(const void* k_bf16, const void* v_bf16, int kv_heads, int64_t n, const vs_indexer_t* w,
+                        const float* t_v, const float* t_s, float eps, float* loss, float* dW_U, float* db_U,
+                        float* dW_V, float* dW_S, void* ws, size_t ws_bytes, void* stream);
+
 /*
  * Number of MFMA tiles the last vs_sparse_prefill that used this workspace executed.  One tile is
  * (32 query rows of one head) x (32 keys): 1024 score elements, 4 * 128 * 1024 flop.  The kernel

@@ -7,5 +7,5 @@ from . import binding  # noqa: F401
 from .binding import (  # noqa: F401
     VsError, IndexerWeights, Budget, rope_apply, index_score, index_score_workspace, select_budget,
     select_budget_workspace, sparse_prefill, sparse_prefill_static, sparse_prefill_workspace, sparse_prefill_tiles, sparse_prefill_counters, validate_lists, dense_prefill, aggregate, aggregate_workspace,
-    version, exported_symbols, library_path,
+    index_train_step, index_train_workspace, version, exported_symbols, library_path,
 )

@@ -15,6 +15,7 @@ EXPORTS = [
     "vs_sparse_prefill_workspace", "vs_sparse_prefill", "vs_sparse_prefill_tiled", "vs_sparse_prefill_chunk",
     "vs_sparse_prefill_static", "vs_dense_prefill", "vs_dense_prefill_chunk", "vs_validate_lists",
     "vs_sparse_prefill_tiles", "vs_sparse_prefill_counters", "vs_aggregate_workspace", "vs_aggregate",
+    "vs_index_train_workspace", "vs_index_train_step",
     "vs_strerror", "vs_last_hip_error", "vs_version",
 ]
 
@@ -75,6 +76,9 @@ def _load():
     L.vs_aggregate_workspace.argtypes = [i32, i32, i32, i64]
     L.vs_aggregate_workspace.restype = sz
     L.vs_aggregate.argtypes = [vp, vp, i32, i32, i64, f32, vp, i32, vp, vp, vp, vp, i32, vp, vp, i32, i32, vp, vp, sz, vp]
+    L.vs_index_train_workspace.argtypes = [i32, i64, i32]
+    L.vs_index_train_workspace.restype = sz
+    L.vs_index_train_step.argtypes = [vp, vp, i32, i64, ctypes.POINTER(_Indexer), vp, vp, f32, vp, vp, vp, vp, vp, vp, sz, vp]
     L.vs_strerror.argtypes = [i32]
     L.vs_strerror.restype = ctypes.c_char_p
     L.vs_last_hip_error.restype = i32
@@ -327,6 +331,29 @@ def aggregate(q, k, a_v, a_s, ws, lse=None, lists=None, recall=None, scale=None,
                                 _ptr(idx_v), _ptr(cnt_v), cap_v, _ptr(idx_s), _ptr(cnt_s), cap_s, index_heads,
                                 _ptr(recall), _ptr(ws), ws_bytes, _stream(stream)), "vs_aggregate")
     return a_v, a_s
+
+
+def index_train_workspace(kv_heads, n, d_h):
+    return _load().vs_index_train_workspace(kv_heads, n, d_h)
+
+
+def index_train_step(k, v, weights, t_v, t_s, loss, dW_U, db_U, dW_V, dW_S, ws, eps=1e-30, stream=None):
+    """Loss KL(A^_v || t_v) + KL(A^_s || t_s) (mean over KV heads) and its gradient with respect to the indexer parameters."""
+    import torch
+    _dev(k, torch.bfloat16, "k"); _dev(v, torch.bfloat16, "v")
+    _dev(t_v, torch.float32, "t_v"); _dev(t_s, torch.float32, "t_s"); _dev(loss, torch.float32, "loss")
+    for name, t in (("dW_U", dW_U), ("db_U", db_U), ("dW_V", dW_V), ("dW_S", dW_S)):
+        _dev(t, torch.float32, name)
+    kv_heads, n, d = k.shape
+    d_h = weights.d_h
+    assert d == 128 and v.shape == k.shape and t_v.shape == (kv_heads, n) and t_s.shape == (kv_heads, n)
+    assert dW_U.shape == (256, d_h) and db_U.numel() == d_h and dW_V.numel() == d_h and dW_S.numel() == d_h and loss.numel() == 1
+    w = weights.c_struct()
+    _check(_load().vs_index_train_step(_ptr(k), _ptr(v), kv_heads, n, ctypes.byref(w), _ptr(t_v), _ptr(t_s), eps, _ptr(loss),
+                                       _ptr(dW_U), _ptr(db_U), _ptr(dW_V), _ptr(dW_S), _ptr(ws),
+                                       0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)),
+           "vs_index_train_step")
+    return loss
 
 
 def dense_prefill(q, k, v, o, lse=None, scale=None, stream=None, pos0=None):

@@ -29,6 +29,8 @@ int main() {
     if (vs_index_score_workspace(8, 131072, 256) == 0 || vs_aggregate_workspace(32, 8, 8, 4096) == 0) return 4;
     EXPECT(vs_aggregate_workspace(32, 8, 8, 0), 0);
     (void)vs_select_budget_workspace(8, 131072);
+    if (vs_index_train_workspace(8, 4096, 256) == 0) return 7;
+    EXPECT(vs_index_train_workspace(8, 4096, 100), 0);
 
     // attention calls
     EXPECT(vs_sparse_prefill(nullptr, p, p, 4, 1, 64, 0.1f, ip, ip, 4, ip, ip, 4, 1, p, nullptr, p, 4096, nullptr), VS_ERR_INVALID_ARG);
@@ -81,6 +83,10 @@ int main() {
            VS_ERR_UNSUPPORTED);
     EXPECT(vs_aggregate(p, p, 4, 1, 64, 0.1f, nullptr, 4, fp, fp, nullptr, nullptr, 0, nullptr, nullptr, 0, 0, nullptr, p, 16, nullptr),
            VS_ERR_WORKSPACE);
+    w.d_h = 256;
+    w.act = 1;
+    EXPECT(vs_index_train_step(p, p, 2, 64, &w, fp, fp, 0.f, fp, fp, fp, fp, fp, p, 1 << 30, nullptr), VS_ERR_INVALID_ARG);
+    EXPECT(vs_index_train_step(p, p, 2, 64, &w, fp, fp, 1e-30f, fp, fp, fp, fp, fp, p, 16, nullptr), VS_ERR_WORKSPACE);
     EXPECT(vs_rope_apply(nullptr, 4, 64, 0, 1e6, 0, nullptr), VS_ERR_INVALID_ARG);
     EXPECT(vs_rope_apply(p, 4, 64, 0, 1e6, 5, nullptr), VS_ERR_INVALID_ARG);
     for (int code = 1; code >= -8; --code)
