@@ -3,11 +3,21 @@
 //
 // The up-projection is the only dense contraction (n x 256 x d_h per head) and runs on the matrix
 // cores as U^T = W_U^T X^T with v_mfma_f32_32x32x16_bf16.  X is bf16 already; the fp32 W_U is split
-// once into two bf16 terms (hi + lo, 16 significant bits together) so that the product keeps fp32
-// class accuracy with two MFMA passes.  With hidden units on the M axis a lane holds 16 hidden
-// units of ONE token, so activation and both down-projections finish in registers and X is read
-// from HBM exactly once; no Z tensor exists.  Logits go to the output arrays and a second kernel
-// normalises them in place.
+// into two bf16 terms (hi + lo, 16 significant bits together) so that the product keeps fp32 class
+// accuracy with two MFMA passes.  With hidden units on the M axis a lane holds 16 hidden units of ONE
+// token, so activation and both down-projections finish in registers; no Z tensor exists.
+//
+// Workgroups are persistent: 8 wavefronts, each keeping the W_U fragments of ITS 32 hidden units in
+// registers for the whole kernel (256 units per workgroup; wider layers are split over workgroups
+// and their partial logits added afterwards), while 128-token tiles of X stream through a double
+// buffer in LDS, read from HBM exactly once.  Per tile every wavefront adds its units' share of the
+// two logits; the shares meet in LDS and wavefronts 0 and 1 write the logits together with the tile's
+// (max, sum of exp) for the softmax over all positions, which a second kernel finishes in place.
+// The wavefronts of a workgroup meet at a barrier per tile and therefore run in phase: left to
+// itself, every SIMD would alternate between a stretch of matrix instructions and a stretch of
+// activation arithmetic.  The four 32-token blocks of a tile are software-pipelined instead: the
+// matrix products of block j + 1 are interleaved, instruction by instruction, with the activation
+// of block j.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
@@ -19,12 +29,19 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kThreads = 256;
-constexpr int kTokensPerWg = 256;          // 4 wavefronts x 2 blocks of 32 tokens
-constexpr int kChunkU = 64;                // hidden units staged in LDS at a time
-constexpr int kWRowBytes = 512 + 32;       // 256 bf16 + pad (conflict-free 16-byte fragment reads)
+constexpr int kThreads = 512;
+constexpr int kWaves = kThreads / 64;
+constexpr int kUnitsPerWg = 32 * kWaves;   // 256
+constexpr int kTokTile = 128;              // tokens per step: four MFMA column blocks of 32
+constexpr int kBlocks = kTokTile / 32;
+constexpr int kXPitch = 512;               // bytes per token row in LDS: K | V in bf16; 16-byte chunk c of row r sits at chunk
+                                           // position c ^ (r % 16), so that 16 consecutive rows read at one chunk hit 16 bank groups
+constexpr int kXBufs = 2;                  // token tiles: one being read, one in flight from HBM
 constexpr int kMaxDh = 1024;
-constexpr size_t kSmemBytes = 2 * kChunkU * kWRowBytes + 3 * kMaxDh * 4;
+constexpr size_t kXBytes = static_cast<size_t>(kTokTile) * kXPitch;
+constexpr size_t kVecOff = kXBufs * kXBytes;                            // b_U, W_V, W_S of the workgroup's units
+constexpr size_t kRedOff = kVecOff + 3 * kUnitsPerWg * 4;          // two parities x wavefronts x tokens x (v, s)
+constexpr size_t kSmemBytes = kRedOff + 2 * kWaves * kTokTile * 8;
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
     uint32_t u = __float_as_uint(f);
@@ -44,172 +61,260 @@ __global__ void split_weights_kernel(const float* __restrict__ W_U, int d_h, uin
     lo[static_cast<size_t>(u) * 256 + k] = f32_to_bf16_rne(rem);
 }
 
+// 16 bytes per lane from global memory straight into LDS: lane L's piece lands at lds_base + 16 L (lds_base is
+// wave-uniform).  The loads complete in the background; the kernel waits (vmcnt) before the barrier that publishes a tile.
+__device__ __forceinline__ void lds_load16(const void* gsrc, const void* lds_base) {
+    const uint32_t base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+        (const __attribute__((address_space(3))) void*)lds_base));
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(base), "v"(gsrc) : "memory", "m0");
+}
+
 __device__ __forceinline__ float half_swap_sum(float x) {
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// erf by the rational approximation 7.1.26 of Abramowitz & Stegun, erf(y) = 1 - (a1 t + ... + a5 t^5) exp(-y^2),
-// t = 1 / (1 + p y), y >= 0, absolute error below 1.5e-7: far inside the 1e-3 relative bar of the scores (the GELU
-// output inherits at most 0.5 |x| * 1.5e-7) and about half the instructions of the library erff.
-__device__ __forceinline__ float erf_as(float x) {
-    const float y = fabsf(x);
-    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, y, 1.f));
-    float poly = fmaf(1.061405429f, t, -1.453152027f);
-    poly = fmaf(poly, t, 1.421413741f);
-    poly = fmaf(poly, t, -0.284496736f);
-    poly = fmaf(poly, t, 0.254829592f);
-    poly *= t;
-    const float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * y * y);
-    return copysignf(fmaf(-poly, e, 1.f), x);
+// GELU (erf form) = x Phi(x) with the normal distribution function written as a logistic function of an odd polynomial,
+// Phi(x) = 1 / (1 + exp(-x P(x^2))), P of degree 4 fitted (minimax over |x| <= 8, own fit) so that x Phi(x) is within
+// 3.1e-6 of the exact value everywhere; beyond the fitted range the leading coefficient keeps the argument growing with
+// the right sign, so Phi saturates at 0 / 1 as it should.  Far inside the 1e-3 relative bar of the scores (256 hidden
+// units with |W| < 1 move a logit by less than 4e-4 even if every error had the same sign) and 8 vector instructions +
+// 2 transcendentals, half of what a rational erf costs.  (A table of Phi in LDS with linear interpolation was measured
+// slower still: its gathers conflict on the banks.)  The coefficients below carry the factor -log2(e) of the exp2.
+__device__ __forceinline__ float gelu_logistic(float x) {
+    constexpr float kL = -1.4426950408889634f;
+    const float x2 = x * x;
+    float p = fmaf(kL * 2.2394289190536126e-06f, x2, kL * -6.118309274724009e-05f);
+    p = fmaf(p, x2, kL * -0.00024962059614273813f);
+    p = fmaf(p, x2, kL * 0.07293742830114522f);
+    p = fmaf(p, x2, kL * 1.5956563098014116f);
+    return x * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(x * p));
 }
 
 template <int ACT>
 __device__ __forceinline__ float activate(float x) {
     if (ACT == 0) return x * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
-    return 0.5f * x * (1.f + erf_as(x * 0.70710678118654752f));
+    return gelu_logistic(x);
 }
 
+struct IndexerParams {
+    const uint16_t* kx;
+    const uint16_t* vx;
+    int heads, n, d_h;
+    const uint16_t* w_hi;
+    const uint16_t* w_lo;
+    const float* b_U;
+    const float* W_V;
+    const float* W_S;
+    float b_V, b_S;
+    float* out_v;                   // logits: a_v / a_s (one slice of hidden units) or the slices' partial sums
+    float* out_s;
+    size_t slice_stride;            // elements between the partial-logit arrays of consecutive slices (0: one slice)
+    float2* part;                   // per (head, direction, 64-token block): (max, sum of exp) of its logits; null with several slices
+    int tiles_per_head;             // 128-token tiles
+    int parts_per_head;             // 64-token statistics blocks
+    int nslices, lanes;             // slices of 256 hidden units; workgroups per slice (a multiple of 8)
+};
+
 template <int ACT>
-__global__ __launch_bounds__(kThreads) void indexer_logits_kernel(const uint16_t* __restrict__ kx, const uint16_t* __restrict__ vx,
-                                                                  int n, int d_h, const uint16_t* __restrict__ w_hi,
-                                                                  const uint16_t* __restrict__ w_lo, const float* __restrict__ b_U,
-                                                                  const float* __restrict__ W_V, const float* __restrict__ W_S,
-                                                                  float b_V, float b_S, float* __restrict__ logit_v,
-                                                                  float* __restrict__ logit_s, float2* __restrict__ part,
-                                                                  int nblk) {
+__global__ __launch_bounds__(kThreads) void indexer_logits_kernel(const IndexerParams p) {
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char* const whi = smem;
-    unsigned char* const wlo = smem + kChunkU * kWRowBytes;
-    float* const sbU = reinterpret_cast<float*>(smem + 2 * kChunkU * kWRowBytes);
-    float* const sWV = sbU + d_h;
-    float* const sWS = sWV + d_h;
+    float* const sbU = reinterpret_cast<float*>(smem + kVecOff);
+    float* const sWV = sbU + kUnitsPerWg;
+    float* const sWS = sWV + kUnitsPerWg;
+    float2* const red = reinterpret_cast<float2*>(smem + kRedOff);
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, hh = lane >> 5;
-    const int g = blockIdx.y;
-    float* const red = reinterpret_cast<float*>(smem);     // 4 wavefronts x (max_v, sum_v, max_s, sum_s); over the weight chunk, after its last use
+    // Workgroup id -> (slice of hidden units, lane of the tile loop).  Consecutive ids go to consecutive XCDs, so the slices
+    // that work on the same tiles are given ids that are multiples of 8 apart: they run on one XCD at about the same time
+    // and all but the first find the tile in that XCD's L2.
+    const int xcd_slot = blockIdx.x & 7, id_hi = blockIdx.x >> 3;
+    const int slice = id_hi % p.nslices;
+    const int tile_lane = (id_hi / p.nslices) * 8 + xcd_slot;
+    const int u_base = slice * kUnitsPerWg;                 // first hidden unit of the workgroup
+    const int units_here = min(kUnitsPerWg, p.d_h - u_base);
+    const int nact = units_here / 32;                       // wavefronts with units (d_h is a multiple of 64)
+    const bool active = wave < nact;
+    const int n = p.n;
 
-    for (int u = tid; u < d_h; u += kThreads) {
-        sbU[u] = b_U[u];
-        sWV[u] = W_V[u];
-        sWS[u] = W_S[u];
+    for (int i = tid; i < kUnitsPerWg; i += kThreads) {
+        const bool ok = i < units_here;
+        sbU[i] = ok ? p.b_U[u_base + i] : 0.f;
+        sWV[i] = ok ? p.W_V[u_base + i] : 0.f;
+        sWS[i] = ok ? p.W_S[u_base + i] : 0.f;
     }
-    const int blk = blockIdx.x;
-    const int tok0 = blk * kTokensPerWg + 64 * wave;
-
-    // X^T fragments: lane holds token col, features 16 kk + 8 hh .. + 7 (kk < 8: K, kk >= 8: V)
-    bf16x8 xf[2][16];
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb) {
-        const int tok = tok0 + 32 * tb + col;
-        const size_t row = (static_cast<size_t>(g) * n + min(tok, n - 1)) * 128 + 8 * hh;
+    // W_U^T fragments of this wavefront's 32 units: A operand, lane = unit row, features 16 kk + 8 hh .. + 7
+    bf16x8 whi[16], wlo[16];
+    if (active) {
+        const size_t row = static_cast<size_t>(u_base + 32 * wave + col) * 256 + 8 * hh;
 #pragma unroll
         for (int kk = 0; kk < 16; ++kk) {
-            uint4 raw = make_uint4(0, 0, 0, 0);
-            if (tok < n) raw = *reinterpret_cast<const uint4*>((kk < 8 ? kx : vx) + row + 16 * (kk & 7));
-            xf[tb][kk] = __builtin_bit_cast(bf16x8, raw);
+            whi[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p.w_hi + row + 16 * kk));
+            wlo[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p.w_lo + row + 16 * kk));
         }
     }
-    float lv[2] = {0.f, 0.f}, ls[2] = {0.f, 0.f};
+    float* const out_v = p.out_v + static_cast<size_t>(slice) * p.slice_stride;
+    float* const out_s = p.out_s + static_cast<size_t>(slice) * p.slice_stride;
 
-    for (int u0 = 0; u0 < d_h; u0 += kChunkU) {
-        __syncthreads();                                   // previous chunk fully consumed
-        for (int i = tid; i < kChunkU * 32; i += kThreads) {   // 32 16-byte pieces per hidden unit
-            const int r = i >> 5, c = i & 31;
-            const size_t src = static_cast<size_t>(u0 + r) * 256 + c * 8;
-            *reinterpret_cast<uint4*>(whi + r * kWRowBytes + c * 16) = *reinterpret_cast<const uint4*>(w_hi + src);
-            *reinterpret_cast<uint4*>(wlo + r * kWRowBytes + c * 16) = *reinterpret_cast<const uint4*>(w_lo + src);
+    // tiles of 64 tokens, never across heads; workgroup b takes tiles b, b + gridDim.x, ...
+    const long long total_tiles = static_cast<long long>(p.heads) * p.tiles_per_head;
+    // Staging: a wavefront instruction deposits 1 KB = two token rows; wavefront w moves rows 16 w .. 16 w + 15 of a tile
+    // with eight instructions.  Lane L fills chunk position L % 32 of its row, i.e. it fetches that row's chunk
+    // (L % 32) ^ (row % 16) (chunks 0-15: K, 16-31: V).
+    const int st_pos = lane & 31;
+    auto load_tile = [&](long long t, int buf) __attribute__((always_inline)) {
+        const int head = static_cast<int>(t / p.tiles_per_head);
+        const int tok0 = static_cast<int>(t % p.tiles_per_head) * kTokTile;
+#pragma unroll
+        for (int i = 0; i < kTokTile / (2 * kWaves); ++i) {
+            const int row0 = (kTokTile / kWaves) * wave + 2 * i;
+            const int row = row0 + hh;
+            const int chunk = st_pos ^ (row & 15);
+            const int tok = min(tok0 + row, n - 1);
+            const uint16_t* src = (chunk < 16 ? p.kx : p.vx) + (static_cast<size_t>(head) * n + tok) * 128 + 8 * (chunk & 15);
+            lds_load16(src, smem + buf * kXBytes + row0 * kXPitch);
         }
-        __syncthreads();
+    };
+    long long tile = tile_lane;
+    const long long stride = p.lanes;
+    if (tile < total_tiles) load_tile(tile, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);                      // the first tile (and the weight fragments) have arrived
+    __syncthreads();
+    const int sw16 = (col & 15) << 4;                        // byte swizzle of this lane's token rows
+    int par = 0;
+    for (; tile < total_tiles; tile += stride, par ^= 1) {
+        const int buf = par;
+        // the other buffer held the tile of the previous step: free since the barrier that ended it
+        if (tile + stride < total_tiles) load_tile(tile + stride, buf ^ 1);
+        const unsigned char* xt = smem + buf * kXBytes;
+        if (active) {
+            // Block j: tokens 32 j + col.  The accumulator starts from the bias; lane (token col, hh) holds hidden units
+            // 32 wave + 8 a + 4 hh + c.  X^T fragments (B operand: lane = token column, features 16 kk + 8 hh .. + 7) come from
+            // LDS a few steps ahead of the products that use them.
+            constexpr int kLook = 4;
+            auto mfma_block = [&](int j, f32x16& acc) __attribute__((always_inline)) {
 #pragma unroll
-        for (int ub = 0; ub < kChunkU / 32; ++ub) {
-            f32x16 acc[2];
-#pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc[tb][e] = 0.f;
-#pragma unroll
-            for (int kk = 0; kk < 16; ++kk) {
-                const int off = (32 * ub + col) * kWRowBytes + kk * 32 + hh * 16;
-                const bf16x8 ah = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(whi + off));
-                const bf16x8 al = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(wlo + off));
-#pragma unroll
-                for (int tb = 0; tb < 2; ++tb) {
-                    acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, xf[tb][kk], acc[tb], 0, 0, 0);
-                    acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, xf[tb][kk], acc[tb], 0, 0, 0);
+                for (int a = 0; a < 4; ++a) {
+                    const float4 bu = *reinterpret_cast<const float4*>(sbU + 32 * wave + 8 * a + 4 * hh);
+                    acc[4 * a] = bu.x;
+                    acc[4 * a + 1] = bu.y;
+                    acc[4 * a + 2] = bu.z;
+                    acc[4 * a + 3] = bu.w;
                 }
-            }
-            // lane holds hidden units u0 + 32 ub + 8 a + 4 hh + c of token `col`
+                uint4 xq[kLook];
+                auto xread = [&](int kk) __attribute__((always_inline)) -> uint4 {
+                    return *reinterpret_cast<const uint4*>(xt + (32 * j + col) * kXPitch + (((2 * kk + hh) << 4) ^ sw16));
+                };
 #pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                const int ub0 = u0 + 32 * ub + 8 * a + 4 * hh;
-                const float4 bu = *reinterpret_cast<const float4*>(sbU + ub0);
-                const float4 wv = *reinterpret_cast<const float4*>(sWV + ub0);
-                const float4 ws = *reinterpret_cast<const float4*>(sWS + ub0);
-                const float bu_[4] = {bu.x, bu.y, bu.z, bu.w}, wv_[4] = {wv.x, wv.y, wv.z, wv.w}, ws_[4] = {ws.x, ws.y, ws.z, ws.w};
+                for (int kk = 0; kk < kLook; ++kk) xq[kk] = xread(kk);
 #pragma unroll
-                for (int tb = 0; tb < 2; ++tb)
+                for (int kk = 0; kk < 16; ++kk) {
+                    const bf16x8 xb = __builtin_bit_cast(bf16x8, xq[kk % kLook]);
+                    if (kk + kLook < 16) xq[kk % kLook] = xread(kk + kLook);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(whi[kk], xb, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wlo[kk], xb, acc, 0, 0, 0);
+                }
+            };
+            auto act_block = [&](int j, const f32x16& acc) __attribute__((always_inline)) {
+                float lv = 0.f, ls = 0.f;
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    const float4 wv = *reinterpret_cast<const float4*>(sWV + 32 * wave + 8 * a + 4 * hh);
+                    const float4 ws = *reinterpret_cast<const float4*>(sWS + 32 * wave + 8 * a + 4 * hh);
+                    const float wv_[4] = {wv.x, wv.y, wv.z, wv.w}, ws_[4] = {ws.x, ws.y, ws.z, ws.w};
 #pragma unroll
                     for (int c = 0; c < 4; ++c) {
-                        const float z = activate<ACT>(acc[tb][4 * a + c] + bu_[c]);
-                        lv[tb] = fmaf(z, wv_[c], lv[tb]);
-                        ls[tb] = fmaf(z, ws_[c], ls[tb]);
+                        const float z = activate<ACT>(acc[4 * a + c]);
+                        lv = fmaf(z, wv_[c], lv);
+                        ls = fmaf(z, ws_[c], ls);
                     }
+                }
+                // both halves of the wavefront hold the same sums afterwards and write the same value
+                red[(par * kWaves + wave) * kTokTile + 32 * j + col] = make_float2(half_swap_sum(lv), half_swap_sum(ls));
+            };
+            f32x16 acc[2];
+            mfma_block(0, acc[0]);
+#pragma unroll
+            for (int j = 0; j < kBlocks; ++j) {
+                if (j + 1 < kBlocks) mfma_block(j + 1, acc[(j + 1) & 1]);
+                act_block(j, acc[j & 1]);
+                if (j + 1 < kBlocks) {
+                    // issue order of this stretch: one matrix instruction, then a few vector instructions, 32 times
+#pragma unroll
+                    for (int i = 0; i < 32; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, ACT == 0 ? 4 : 6, 0);
+                    }
+                }
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);                  // this wavefront's pieces of the next tile have landed
+        __syncthreads();
+        if (wave < kTokTile / 64) {
+            // 64 tokens of the tile per wavefront: add the wavefronts' shares, write the logits, fold the softmax statistics
+            const int head = static_cast<int>(tile / p.tiles_per_head);
+            const int tile_in_head = static_cast<int>(tile % p.tiles_per_head);
+            const int tt = 64 * wave + lane;
+            const int tok = tile_in_head * kTokTile + tt;
+            float v = 0.f, s2 = 0.f;
+            for (int w = 0; w < nact; ++w) {
+                const float2 r = red[(par * kWaves + w) * kTokTile + tt];
+                v += r.x;
+                s2 += r.y;
+            }
+            if (slice == 0) {                               // the scalar output biases enter once
+                v += p.b_V;
+                s2 += p.b_S;
+            }
+            const bool ok = tok < n;
+            if (ok) {
+                out_v[static_cast<size_t>(head) * n + tok] = v;
+                out_s[static_cast<size_t>(head) * n + tok] = s2;
+            }
+            if (p.part) {
+                float mv = ok ? v : -INFINITY, ms = ok ? s2 : -INFINITY;
+#pragma unroll
+                for (int d = 32; d >= 1; d >>= 1) {
+                    mv = fmaxf(mv, __shfl_xor(mv, d));
+                    ms = fmaxf(ms, __shfl_xor(ms, d));
+                }
+                float ev = ok ? expf(v - mv) : 0.f, es = ok ? expf(s2 - ms) : 0.f;
+#pragma unroll
+                for (int d = 32; d >= 1; d >>= 1) {
+                    ev += __shfl_xor(ev, d);
+                    es += __shfl_xor(es, d);
+                }
+                const int pt = (kTokTile / 64) * tile_in_head + wave;           // statistics per 64 tokens
+                if (lane == 0 && pt < p.parts_per_head) {
+                    p.part[(static_cast<size_t>(head) * 2 + 0) * p.parts_per_head + pt] = make_float2(mv, ev);
+                    p.part[(static_cast<size_t>(head) * 2 + 1) * p.parts_per_head + pt] = make_float2(ms, es);
+                }
             }
         }
     }
-    // logits out; (max, sum of exp) of the block's tokens per direction for the softmax over all positions
-    float mv = -INFINITY, ms = -INFINITY, v2[2], s2[2];
+}
+
+// Several slices of hidden units: logits = sum of the slices' partial logits, written to the output arrays together with
+// the (max, sum of exp) of every 64-token block.  One wavefront per block.
+__global__ __launch_bounds__(64) void combine_slices_kernel(const float* __restrict__ part_v, const float* __restrict__ part_s,
+                                                            size_t slice_stride, int nslices, int n, float* __restrict__ a_v,
+                                                            float* __restrict__ a_s, float2* __restrict__ part, int parts_per_head) {
+    const int head = blockIdx.y, tile = blockIdx.x, dir = blockIdx.z, lane = threadIdx.x;
+    const int tok = tile * 64 + lane;
+    const bool ok = tok < n;
+    const float* src = (dir == 0 ? part_v : part_s) + static_cast<size_t>(head) * n + tok;
+    float x = 0.f;
+    if (ok)
+        for (int s = 0; s < nslices; ++s) x += src[static_cast<size_t>(s) * slice_stride];
+    if (ok) (dir == 0 ? a_v : a_s)[static_cast<size_t>(head) * n + tok] = x;
+    float m = ok ? x : -INFINITY;
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb) {
-        v2[tb] = half_swap_sum(lv[tb]) + b_V;
-        s2[tb] = half_swap_sum(ls[tb]) + b_S;
-        const int tok = tok0 + 32 * tb + col;
-        if (tok < n) {
-            if (hh == 0) {
-                logit_v[static_cast<size_t>(g) * n + tok] = v2[tb];
-                logit_s[static_cast<size_t>(g) * n + tok] = s2[tb];
-            }
-            mv = fmaxf(mv, v2[tb]);
-            ms = fmaxf(ms, s2[tb]);
-        }
-    }
+    for (int d = 32; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d));
+    float e = ok ? expf(x - m) : 0.f;
 #pragma unroll
-    for (int d = 16; d >= 1; d >>= 1) {                     // both halves hold the same 32 tokens
-        mv = fmaxf(mv, __shfl_xor(mv, d));
-        ms = fmaxf(ms, __shfl_xor(ms, d));
-    }
-    float ev = 0.f, es = 0.f;
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb) {
-        if (tok0 + 32 * tb + col < n) {
-            ev += expf(v2[tb] - mv);
-            es += expf(s2[tb] - ms);
-        }
-    }
-#pragma unroll
-    for (int d = 16; d >= 1; d >>= 1) {
-        ev += __shfl_xor(ev, d);
-        es += __shfl_xor(es, d);
-    }
-    __syncthreads();                                        // every wavefront is done with the weight chunk
-    if (lane == 0) {
-        red[4 * wave] = mv;
-        red[4 * wave + 1] = ev;
-        red[4 * wave + 2] = ms;
-        red[4 * wave + 3] = es;
-    }
-    __syncthreads();
-    if (tid < 2) {                                          // thread 0: vertical, thread 1: slash
-        float m = -INFINITY, e = 0.f;
-        for (int w = 0; w < 4; ++w) m = fmaxf(m, red[4 * w + 2 * tid]);
-        for (int w = 0; w < 4; ++w) {
-            const float mw = red[4 * w + 2 * tid];
-            if (mw > -INFINITY) e += red[4 * w + 2 * tid + 1] * expf(mw - m);
-        }
-        part[(static_cast<size_t>(g) * 2 + tid) * nblk + blk] = make_float2(m, e);
-    }
+    for (int d = 32; d >= 1; d >>= 1) e += __shfl_xor(e, d);
+    if (lane == 0) part[(static_cast<size_t>(head) * 2 + dir) * parts_per_head + tile] = make_float2(m, e);
 }
 
 // Second stage of the softmax over the n positions of one (head, direction): every workgroup folds the per-block
@@ -246,8 +351,9 @@ __global__ __launch_bounds__(256) void softmax_finish_kernel(float* a_v, float* 
 }
 
 struct IndexerWs {
-    size_t hi_off, lo_off, part_off, total;
-    int nblk;
+    size_t hi_off, lo_off, part_off, plog_off, total;
+    size_t slice_stride;            // elements per slice of partial logits (one direction)
+    int tiles_per_head, parts_per_head, nslices;
 };
 
 IndexerWs indexer_ws_layout(int kv_heads, int64_t n, int d_h) {
@@ -255,8 +361,12 @@ IndexerWs indexer_ws_layout(int kv_heads, int64_t n, int d_h) {
     w.hi_off = 0;
     w.lo_off = vs::round_up(static_cast<size_t>(d_h) * 256 * 2, 256);
     w.part_off = 2 * w.lo_off;
-    w.nblk = static_cast<int>((n + kTokensPerWg - 1) / kTokensPerWg);
-    w.total = w.part_off + vs::round_up(static_cast<size_t>(kv_heads) * 2 * w.nblk * sizeof(float2), 256);
+    w.tiles_per_head = static_cast<int>((n + kTokTile - 1) / kTokTile);
+    w.parts_per_head = static_cast<int>((n + 63) / 64);
+    w.nslices = (d_h + kUnitsPerWg - 1) / kUnitsPerWg;
+    w.plog_off = w.part_off + vs::round_up(static_cast<size_t>(kv_heads) * 2 * w.parts_per_head * sizeof(float2), 256);
+    w.slice_stride = w.nslices > 1 ? vs::round_up(static_cast<size_t>(kv_heads) * n, 64) : 0;
+    w.total = w.plog_off + (w.nslices > 1 ? 2 * static_cast<size_t>(w.nslices) * w.slice_stride * 4 : 0);
     return w;
 }
 
@@ -287,32 +397,70 @@ int vs_index_score(const void* k_bf16, const void* v_bf16, int kv_heads, int64_t
     uint16_t* lo = reinterpret_cast<uint16_t*>(static_cast<unsigned char*>(ws) + lay.lo_off);
 
     static vs::PerDeviceOnce once;
-    const int rc_once = once.run(nullptr, [](int) -> int {
+    static int cus_of[vs::kMaxDevices];
+    int dev = 0;
+    const int rc_once = once.run(&dev, [](int d) -> int {
         VS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&indexer_logits_kernel<0>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kSmemBytes)));
         VS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&indexer_logits_kernel<1>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kSmemBytes)));
+        int cus = 0;
+        VS_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, d));
+        cus_of[d] = cus > 0 ? cus : 256;
         return VS_OK;
     });
     if (rc_once != VS_OK) return rc_once;
     hipLaunchKernelGGL(split_weights_kernel, dim3((w->d_h * 256 + 255) / 256), dim3(256), 0, st, w->W_U, w->d_h, hi, lo);
     VS_LAUNCH_CHECK();
-    float2* part = reinterpret_cast<float2*>(static_cast<unsigned char*>(ws) + lay.part_off);
-    // one workgroup per block of 256 tokens
-    const dim3 grid(static_cast<unsigned>(lay.nblk), kv_heads);
-    // LDS: one 64-unit chunk of both weight halves + the three per-unit vectors; two workgroups per CU up to d_h = 1024
-    const size_t smem = 2 * kChunkU * kWRowBytes + 3 * static_cast<size_t>(w->d_h) * 4;
-    const uint16_t* kx = static_cast<const uint16_t*>(k_bf16);
-    const uint16_t* vx = static_cast<const uint16_t*>(v_bf16);
-    if (w->act == 0)
-        hipLaunchKernelGGL(indexer_logits_kernel<0>, grid, dim3(kThreads), smem, st, kx, vx, static_cast<int>(n), w->d_h,
-                           hi, lo, w->b_U, w->W_V, w->W_S, w->b_V, w->b_S, a_v, a_s, part, lay.nblk);
-    else
-        hipLaunchKernelGGL(indexer_logits_kernel<1>, grid, dim3(kThreads), smem, st, kx, vx, static_cast<int>(n), w->d_h,
-                           hi, lo, w->b_U, w->W_V, w->W_S, w->b_V, w->b_S, a_v, a_s, part, lay.nblk);
+    unsigned char* base = static_cast<unsigned char*>(ws);
+    float2* part = reinterpret_cast<float2*>(base + lay.part_off);
+    IndexerParams p{};
+    p.kx = static_cast<const uint16_t*>(k_bf16);
+    p.vx = static_cast<const uint16_t*>(v_bf16);
+    p.heads = kv_heads;
+    p.n = static_cast<int>(n);
+    p.d_h = w->d_h;
+    p.w_hi = hi;
+    p.w_lo = lo;
+    p.b_U = w->b_U;
+    p.W_V = w->W_V;
+    p.W_S = w->W_S;
+    p.b_V = w->b_V;
+    p.b_S = w->b_S;
+    p.tiles_per_head = lay.tiles_per_head;
+    p.parts_per_head = lay.parts_per_head;
+    float* plog_v = reinterpret_cast<float*>(base + lay.plog_off);
+    float* plog_s = plog_v + static_cast<size_t>(lay.nslices) * lay.slice_stride;
+    if (lay.nslices == 1) {
+        p.out_v = a_v;
+        p.out_s = a_s;
+        p.slice_stride = 0;
+        p.part = part;
+    } else {
+        p.out_v = plog_v;
+        p.out_s = plog_s;
+        p.slice_stride = lay.slice_stride;
+        p.part = nullptr;
+    }
+    // persistent workgroups of 8 wavefronts, one per compute unit, shared out over the slices of 256 hidden units
+    const long long total_tiles = static_cast<long long>(kv_heads) * lay.tiles_per_head;
+    long long lanes = (cus_of[dev] / lay.nslices) & ~7;
+    if (lanes < 8) lanes = 8;
+    const long long need = (total_tiles + 7) & ~7ll;
+    if (lanes > need) lanes = need;
+    p.nslices = lay.nslices;
+    p.lanes = static_cast<int>(lanes);
+    const dim3 grid(static_cast<unsigned>(lanes * lay.nslices));
+    if (w->act == 0) hipLaunchKernelGGL(indexer_logits_kernel<0>, grid, dim3(kThreads), kSmemBytes, st, p);
+    else hipLaunchKernelGGL(indexer_logits_kernel<1>, grid, dim3(kThreads), kSmemBytes, st, p);
     VS_LAUNCH_CHECK();
+    if (lay.nslices > 1) {
+        hipLaunchKernelGGL(combine_slices_kernel, dim3(lay.parts_per_head, kv_heads, 2), dim3(64), 0, st, plog_v, plog_s,
+                           lay.slice_stride, lay.nslices, static_cast<int>(n), a_v, a_s, part, lay.parts_per_head);
+        VS_LAUNCH_CHECK();
+    }
     hipLaunchKernelGGL(softmax_finish_kernel, dim3(static_cast<unsigned>((n + 1023) / 1024), kv_heads, 2), dim3(256), 0, st, a_v,
-                       a_s, static_cast<int>(n), part, lay.nblk);
+                       a_s, static_cast<int>(n), part, lay.parts_per_head);
     VS_LAUNCH_CHECK();
     return VS_OK;
 }
