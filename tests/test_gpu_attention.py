@@ -57,7 +57,7 @@ def _random_sets(rng, n, heads, nv, ns, runs=True):
     (4, 4, 640, 20, 60, False),        # G = 1: 256-row tiles
     (4, 2, 900, 50, 100, False),       # G = 2
     (8, 2, 700, 40, 80, True),         # one list per query head
-    (40, 40, 200, 10, 20, False),      # more than 32 KV heads: no work queues, one workgroup per unit
+    (40, 40, 200, 10, 20, False),      # more KV heads (work queues) than the 32 of one layer
     (80, 40, 150, 8, 12, False),       # the same with two query heads per KV head
     (16, 2, 500, 30, 50, False),       # G = 8: two workgroups per tile
 ])
