@@ -35,8 +35,11 @@ def test_strerror_and_workspace_queries():
         assert L.vs_strerror(code) not in (b"ok", b"unknown status")
     assert vs.sparse_prefill_workspace(32, 8, 8, 131072) > 3 * 8 * 131072 // 8 // 2
     assert vs.sparse_prefill_workspace(32, 8, 5, 131072) == 0          # index_heads must be q_heads or kv_heads
-    # two bf16 halves of W_U + one (max, sum) pair per head, direction and block of 256 tokens
-    assert vs.index_score_workspace(8, 131072, 256) == 2 * 256 * 256 * 2 + 8 * 2 * 512 * 8
+    # two bf16 halves of W_U + one (max, sum) pair per head, direction and block of 64 tokens
+    assert vs.index_score_workspace(8, 131072, 256) == 2 * 256 * 256 * 2 + 8 * 2 * 2048 * 8
+    # wider layers also hold the partial logits of every slice of 256 hidden units
+    assert vs.index_score_workspace(8, 131072, 1024) == 2 * 1024 * 256 * 2 + 8 * 2 * 2048 * 8 + 2 * 4 * 8 * 131072 * 4
+    assert vs.index_train_workspace(8, 4096, 256) > vs.index_score_workspace(8, 4096, 256)
     assert vs.index_score_workspace(8, 131072, 100) == 0               # d_h must be a multiple of 64
     assert vs.select_budget_workspace(8, 131072) == 0
 
