@@ -269,7 +269,18 @@ def sweep(w, args, t_dense, dense_flop, dense_tiles, causal_pairs):
     res["aggregate_recall"] = {"ms": t, "qk_tflops": 2 * dense_flop / 2 / (t * 1e-3) / 1e12,
                                "sum_a_v": float(t_v.sum(dim=1).mean()), "sum_a_s": float(t_s.sum(dim=1).mean()),
                                "attention_recall_per_kv_head": [float(x) for x in rec.cpu()]}
-    del wsa, t_v, t_s
+    # one distillation step of the default indexer (GELU / 256) on these targets: loss + all parameter gradients
+    wt = w.weights
+    wst = torch.empty(vs.index_train_workspace(w.hk, n, wt.d_h), dtype=torch.uint8, device="cuda")
+    f32 = lambda *shape: torch.empty(shape, dtype=torch.float32, device="cuda")
+    loss, dW_U, db_U, dW_V, dW_S = f32(1), f32(256, wt.d_h), f32(wt.d_h), f32(wt.d_h), f32(wt.d_h)
+    ts = lambda: vs.index_train_step(w.k, w.v, wt, t_v, t_s, loss, dW_U, db_U, dW_V, dW_S, wst)
+    ts()
+    torch.cuda.synchronize()
+    t = float(np.median(timed(ts, 5)))
+    res["index_train_step"] = {"ms": t, "loss": float(loss.cpu()),
+                               "mfma_tflops": 3 * 2.0 * 2 * 256 * wt.d_h * w.hk * n / (t * 1e-3) / 1e12}
+    del wsa, t_v, t_s, wst
     # 36 layers, seeded tau per layer (whole-prefill attention path of a 36-layer model at this length)
     taus = np.random.default_rng(synth.config_seed(args.config)).uniform(0.8, 0.95, size=36)
     def layers():
