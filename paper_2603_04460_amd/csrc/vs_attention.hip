@@ -59,13 +59,11 @@ constexpr int kWaves = kThreads / 64;
 constexpr int kRing = 4;                       // ring of two stages of two tiles
 constexpr int kListCap = 128;                  // block list: kListCap / nsub entries per pass
 constexpr int kLdsBudget = 80 * 1024;          // per workgroup: two of them share the 160 KB of a compute unit
-// LDS: ring | block list | column word per listed block | offset windows per (sub-block, listed block) | scratch |
-// gather list (entries per pass)
-constexpr int kGatherCap = 2496;
-constexpr size_t kListOff = kRing * kSlotBytes;
-constexpr size_t kListVwOff = kListOff + kListCap * 4;
-constexpr size_t kListWOff = kListVwOff + kListCap * 4;
-constexpr size_t kScratchOff = kListWOff + kListCap * 8;
+// LDS: ring | tile records per (sub-block, listed block) | scratch | gather list (entries per pass)
+constexpr int kGatherCap = 2432;
+constexpr int kRecPad = 4;                     // dead records after a sub-block's last listed block (a step looks one stage ahead)
+constexpr size_t kListRecOff = kRing * kSlotBytes;           // 16-byte tile record per (sub-block, listed block)
+constexpr size_t kScratchOff = kListRecOff + (kListCap + 4 * kRecPad) * 16;
 constexpr size_t kGatherOff = kScratchOff + 128;
 constexpr size_t kLdsBytes = kGatherOff + kGatherCap * 4;
 static_assert(kLdsBytes <= kLdsBudget, "two workgroups per compute unit");
@@ -76,9 +74,7 @@ static_assert(kGatherCap % 64 == 0, "whole stages");
 __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnParams p) {
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char* const kvbuf = smem;
-    int* const list = reinterpret_cast<int*>(smem + kListOff);
-    uint32_t* const list_vw = reinterpret_cast<uint32_t*>(smem + kListVwOff);
-    uint64_t* const list_w = reinterpret_cast<uint64_t*>(smem + kListWOff);
+    uint4* const list_rec = reinterpret_cast<uint4*>(smem + kListRecOff);
     int* const wtot = reinterpret_cast<int*>(smem + kScratchOff);
     int* const glist = reinterpret_cast<int*>(smem + kGatherOff);
 
@@ -272,47 +268,57 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
     // per-wavefront description of a tile: live (anything kept for this row block), need (a mask is required)
     struct TileInfo {
         bool live, need;
-        uint64_t w, cz;          // contiguous tile: selected offsets / causal offsets window
-        uint32_t fw, xw;         // contiguous tile: keys kept for every causal row / keys dropped (listed columns)
+        const uint4* rec;        // contiguous tile: its record in LDS
         const int* cols;         // gathered tile: its 32 column numbers in LDS
     };
     const int bcap = kListCap / nsub;                        // listed blocks per round
     const int my_sub = wave / p.hc;
-    // t: position in the block list
-    auto block_info = [&](int t) __attribute__((always_inline)) -> TileInfo {
-        TileInfo ti{false, false, 0ull, 0ull, 0u, 0u, nullptr};
-        const int b = __builtin_amdgcn_readfirstlane(list[t]);
-        const int dlt = my_i0 - 32 * b;                      // offset of (row 0, key 0) of the 32x32 tile
-        if (dlt < -31 || !my_rows) return ti;                // every key lies after every row / padding rows
-        ti.cz = dlt >= 31 ? kAll63 : ((kAll63 << (31 - dlt)) & kAll63);   // offsets >= 0
-        // selected offsets dlt-31 .. dlt+31 at bits 0..62 and the block's column word, both prepared with the list
-        ti.w = uniform64(list_w[my_sub * bcap + t]);
-        ti.xw = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(list_vw[t]));
+    // Tile record of a listed block for one 32-row sub-block, made once per unit by the thread that lists the block, so
+    // that a step of the tile loop reads one flag word (scalar instructions cost this loop as much as vector ones):
+    //   x, y: 64-bit window wz; lane (q, h) keeps key kj iff bit 31 + q - kj of wz is set and bit kj of kw (word z) is:
+    //         element-exact mode: wz = selected offsets dlt-31 .. dlt+31, kw = columns not listed
+    //         tile-granular mode: wz = causal offsets, kw = keys that some row of the block reaches through a selected
+    //         offset, listed columns taken out
+    //   w: bit 0 live, bit 1 a mask is needed, bits 2..: the key block (so that one word per tile tells a step all it
+    //      needs for the staging loads and the tests; the rest is read only where a mask is applied)
+    // sub_i0: first row of the sub-block; b: key block; w: the offset window prepared with the diagonal list; xw: the block's
+    // column word
+    auto make_record = [&](int sub_i0, int b, uint64_t w, uint32_t xw) __attribute__((always_inline)) -> uint4 {
+        const int dlt = sub_i0 - 32 * b;                     // offset of (row 0, key 0) of the 32x32 tile
+        uint64_t wz = w;
+        uint32_t kw = ~xw;
+        bool live = w != 0ull, need = w != kAll63 || xw != 0u;
         if (p.gran == 32) {
             // Tile-granular slash: key kj is kept for every causal row of this 32-row block if ANY of its rows reaches it
             // through a selected offset, i.e. if the window has a bit in [31 - kj, 62 - kj].
             // x bit s = OR of window bits s .. s+len-1, len = rows of this block that exist (32 except at the end of
             // the sequence): doubling up to the largest power of two pw <= len, then two overlapping windows
-            const int len = min(32, n_pos - my_i0);
-            uint64_t x = ti.w;
+            const int len = max(1, min(32, n_pos - sub_i0));
+            uint64_t x = w;
             int pw = 1;
             while (2 * pw <= len) {
                 x |= x >> pw;
                 pw *= 2;
             }
             x |= x >> (len - pw);
-            ti.fw = __builtin_bitreverse32(static_cast<uint32_t>(x)) & ~ti.xw;
-            ti.w = 0ull;
-            ti.live = ti.fw != 0u && ti.cz != 0ull;
-            ti.need = !(ti.fw == 0xffffffffu && ti.cz == kAll63);
-            return ti;
+            wz = dlt >= 31 ? kAll63 : (dlt < -31 ? 0ull : ((kAll63 << (31 - dlt)) & kAll63));   // offsets >= 0
+            kw = __builtin_bitreverse32(static_cast<uint32_t>(x)) & ~xw;
+            live = kw != 0u && wz != 0ull;
+            need = !(kw == 0xffffffffu && wz == kAll63);
         }
-        ti.live = ti.w != 0ull;
-        ti.need = ti.w != kAll63 || ti.xw != 0u;
-        return ti;
+        if (dlt < -31 || sub_i0 >= n_pos) live = false;      // every key lies after every row / padding rows
+        return make_uint4(static_cast<uint32_t>(wz), static_cast<uint32_t>(wz >> 32), kw,
+                          (live ? 1u : 0u) | (need ? 2u : 0u) | (static_cast<uint32_t>(b) << 2));
+    };
+    const int rcap = bcap + kRecPad;                         // records per sub-block
+    const uint4* const my_rec = list_rec + my_sub * rcap;
+    // t: position in the block list; d: word w of its record
+    auto block_info = [&](int t, uint32_t d) __attribute__((always_inline)) -> TileInfo {
+        const uint32_t fl = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(d));
+        return TileInfo{(fl & 1u) != 0u, (fl & 2u) != 0u, my_rec + t, nullptr};
     };
     auto gather_info = [&](const int* cols) __attribute__((always_inline)) -> TileInfo {
-        TileInfo ti{false, false, 0ull, 0ull, 0u, 0u, cols};
+        TileInfo ti{false, false, nullptr, cols};
         const int cmin = cols[0], cmax = cols[31];           // ascending, INT_MAX padding
         ti.live = my_rows && cmin <= my_i0 + 31;
         ti.need = cmax > my_i0;
@@ -331,66 +337,83 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
                 if (c4.w > row) acc[4 * a + 3] = NEG_INF;
             }
         } else {
-            mask_elements<0>(acc, lane_keep_bits(ti.w, ti.cz, ti.fw, ti.xw, qi + 4 - 4 * hh, 4 - 4 * hh), __float_as_uint(NEG_INF));
+            const uint4 r = *ti.rec;                         // one broadcast read
+            const uint64_t wz = (static_cast<uint64_t>(r.y) << 32) | r.x;
+            const uint32_t keep = static_cast<uint32_t>(wz >> (qi + 4 - 4 * hh)) & (__builtin_bitreverse32(r.z) >> (4 - 4 * hh));
+            mask_elements<0>(acc, keep, __float_as_uint(NEG_INF));
         }
     };
 
     // ---- pipeline over the tiles of one phase ----
-    // GATHER == false: tile t is key block list[t];  GATHER == true: tile t is glist[32 t .. 32 t + 31].
+    // GATHER == false: tile t is the key block of record t;  GATHER == true: tile t is glist[32 t .. 32 t + 31].
     // A stage is two tiles (64 keys).  Two stages live in LDS: step s computes on stage s and refills the buffer of
     // stage s-1 with stage s+1, whose global loads are started at the top of the step.  One barrier per step.  The two
     // tiles of a stage go through one softmax (one row maximum, one rescale decision) and their matrix products are
     // issued as independent chains.
     // nfull: leading stages in which this wavefront's row block keeps every key of both tiles (no mask, nothing to skip)
-    auto run_phase = [&](int ntiles, auto gather_tag, int nfull) __attribute__((always_inline)) {
+    // primed: stage 0 of this phase was requested by the previous phase's last step (into the buffer it had free);
+    // chain: this (block) phase is followed by a gather phase whose list is ready, so its last step requests that phase's
+    // stage 0 and the pipeline does not drain between the two.
+    int buf = 0;                                             // buffer of the current stage; the next stage goes to the other one
+    auto run_phase = [&](int ntiles, auto gather_tag, int nfull, bool primed, bool chain) __attribute__((always_inline)) {
         constexpr bool GATHER = decltype(gather_tag)::value;
         if (ntiles == 0) return;
         const int nstages = (ntiles + 1) >> 1;
         if (GATHER) staged_gather += static_cast<unsigned int>(ntiles);   // 32-key tiles this workgroup stages in LDS
         else staged_block += static_cast<unsigned int>(ntiles);
-        auto stage_rows = [&](int st, int (&rows)[2][2]) __attribute__((always_inline)) {
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int t = 2 * st + u;
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    // rows past the sequence and tiles past the list read another row instead: their scores are masked,
-                    // so the loads need no predicate
-                    const int r = st_row + 16 * h;
-                    int row = 0;
-                    if (GATHER) row = min(glist[32 * t + r], n - 1);       // the list is padded with INT_MAX to a whole stage
-                    else if (t < ntiles) row = min(32 * list[t] + r, n - 1);
-                    rows[u][h] = row;
-                }
+        // Descriptor words of the two tiles of stage st (block phase): one LDS instruction; the records are padded with dead
+        // entries, so a stage past the list reads as "not live, block 0".
+        auto stage_desc = [&](int st, uint32_t (&d)[2]) __attribute__((always_inline)) {
+            d[0] = d[1] = 0u;
+            if constexpr (!GATHER) {
+                d[0] = my_rec[2 * st].w;
+                d[1] = my_rec[2 * st + 1].w;
             }
         };
-        auto info = [&](int t) __attribute__((always_inline)) -> TileInfo {
-            if (t >= ntiles) return TileInfo{false, false, 0ull, 0ull, 0u, 0u, nullptr};
-            if (GATHER) return gather_info(glist + 32 * t);
-            return block_info(t);
+        // rows past the sequence and tiles past the list read another row instead: their scores are masked, so the loads
+        // need no predicate
+        auto stage_rows = [&](int st, const uint32_t (&d)[2], int (&rows)[2][2]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int r = st_row + 16 * h;
+                    if (GATHER) rows[u][h] = min(glist[32 * (2 * st + u) + r], n - 1);   // padded with INT_MAX to a whole stage
+                    else rows[u][h] = min(static_cast<int>(d[u] >> 2) * 32 + r, n - 1);
+                }
+        };
+        auto info = [&](int t, uint32_t d) __attribute__((always_inline)) -> TileInfo {
+            if (GATHER) {
+                if (t >= ntiles) return TileInfo{false, false, nullptr, nullptr};
+                return gather_info(glist + 32 * t);
+            }
+            return block_info(t, d);
         };
         // Every vector memory load issued so far (the Q fragments) is waited for here, once.  Left pending, the first
         // use of Q inside the loop would wait for "all loads", including the staging loads issued just before it.
         __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0), other counters untouched
         int rows[2][2];
-        stage_rows(0, rows);
-        load_stage(rows, 0);
-        __builtin_amdgcn_s_waitcnt(0x0F70);                  // the barrier publishes only what has arrived
+        uint32_t d0[2];
+        stage_desc(0, d0);
+        if (!primed) {
+            stage_rows(0, d0, rows);
+            load_stage(rows, buf);
+            __builtin_amdgcn_s_waitcnt(0x0F70);              // the barrier publishes only what has arrived
+        }
         __syncthreads();
         bf16x8 k0[8], k1[8], vf[8], p0[2], p1[2];
         nfull = min(nfull, nstages);
-        TileInfo a{false, false, 0ull, 0ull, 0u, 0u, nullptr}, b = a;
+        TileInfo a{false, false, nullptr, nullptr}, b = a;
         if (nfull == 0) {
-            a = info(0);
-            b = info(1);
+            a = info(0, d0[0]);
+            b = info(1, d0[1]);
         }
-        auto pv = [&](const bf16x8 (&pk)[2]) __attribute__((always_inline)) {
+        auto pv = [&](const bf16x8 (&pk)[2], const bf16x8 (&vf)[8]) __attribute__((always_inline)) {
 #pragma unroll
             for (int t = 0; t < 2; ++t)                      // the four d-blocks in turn: consecutive MFMAs are independent
 #pragma unroll
                 for (int db = 0; db < 4; ++db) oacc[db] = mfma32(vf[2 * db + t], pk[t], oacc[db]);
         };
-        int buf = 0;                                         // buffer of stage st; stage st+1 goes to the other one
         // one step
         // FULL: both tiles are kept whole by this row block: no tile descriptions, no masks, no tests
         auto step = [&](int st, auto full_tag) __attribute__((always_inline)) {
@@ -402,14 +425,22 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
             const int buf1 = buf ^ 1;
             // list / bitmap words of the next stage are requested before the staging loads: the memory counters retire
             // in order, so waiting for them does not wait for the (younger) staging loads
-            TileInfo na{false, false, 0ull, 0ull, 0u, 0u, nullptr}, nb = na;
+            TileInfo na{false, false, nullptr, nullptr}, nb = na;
+            uint32_t d[2];
+            stage_desc(st + 1, d);
             if constexpr (!FULL) {
-                na = info(2 * st + 2);
-                nb = info(2 * st + 3);
+                na = info(2 * st + 2, d[0]);
+                nb = info(2 * st + 3, d[1]);
             }
             const bool more = st + 1 < nstages;
             if (more) {                                      // into the buffer of stage st-1, free since the barrier
-                stage_rows(st + 1, rows);
+                stage_rows(st + 1, d, rows);
+                load_stage(rows, buf1);
+            } else if (!GATHER && chain) {                   // first stage of the gather phase that follows
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) rows[u][h] = min(glist[32 * u + st_row + 16 * h], n - 1);
                 load_stage(rows, buf1);
             }
             // scores of the two tiles: defined only where the tile is live (every later use is under the same test), so
@@ -456,11 +487,11 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
                 l_run += lsum;
                 if (alive) {
                     read_v(2 * buf, vf);
-                    pv(p0);
+                    pv(p0, vf);
                 }
                 if (blive) {
                     read_v(2 * buf + 1, vf);
-                    pv(p1);
+                    pv(p1, vf);
                 }
             }
             a = na;
@@ -470,11 +501,15 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
         int st = 0;
         for (; st < nfull; ++st) step(st, std::true_type{});
         if (st > 0 && st < nstages) {
-            a = info(2 * st);
-            b = info(2 * st + 1);
+            stage_desc(st, d0);
+            a = info(2 * st, d0[0]);
+            b = info(2 * st + 1, d0[1]);
         }
         for (; st < nstages; ++st) step(st, std::false_type{});
-        __syncthreads();                                     // the ring and the list are reused by the next phase
+        if (!(!GATHER && chain)) {
+            __syncthreads();                                 // the ring and the list are reused by the next phase
+            buf = 0;
+        }
     };
 
     // ---- phases ----
@@ -508,23 +543,29 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
         //    blocks.  Each listed block gets its column word and, per 32-row sub-block of the tile, its offset window.
         //    The first round of the gather list is copied with the first block round (one barrier for both).
         int gcount = -1;
+        bool chained = false;
         for (int rbase = 0; rbase < ndiag; rbase += bcap) {
             const int count = min(bcap, ndiag - rbase);
-            for (int e = tid; e < count; e += kThreads) {
+            if (tid < count) {                               // bcap < kThreads: one entry per thread
+                const int e = tid;
                 const int b = qb0 - dl[rbase + e];
-                list[e] = b;
-                list_vw[e] = vbit[b];
-                for (int r = 0; r < nsub; ++r) list_w[r * bcap + e] = wl[static_cast<size_t>(rbase + e) * 4 + r];
+                const uint32_t xw = vbit[b];
+                for (int r = 0; r < nsub; ++r)
+                    list_rec[r * rcap + e] = make_record(i0 + 32 * r, b, wl[static_cast<size_t>(rbase + e) * 4 + r], xw);
+            } else if (tid < count + kRecPad) {
+                for (int r = 0; r < nsub; ++r) list_rec[r * rcap + tid] = make_uint4(0u, 0u, 0u, 0u);
             }
             if (gcount < 0) gcount = gather_round();         // ends with a barrier
             else __syncthreads();
-            run_phase(count, std::false_type{}, 0);
+            chained = rbase + bcap >= ndiag && gcount > 0;   // last block round, and a gather phase follows
+            run_phase(count, std::false_type{}, 0, false, chained);
         }
         // 2. vertical part: the causal columns, gathered row by row
         if (gcount < 0) gcount = gather_round();
         while (true) {
             const int nfull = max(0, min(nbefore - first, gcount)) >> 6;
-            run_phase((gcount + 31) >> 5, std::true_type{}, nfull);
+            run_phase((gcount + 31) >> 5, std::true_type{}, nfull, chained, false);
+            chained = false;
             if (cursor >= ncand) break;
             gcount = gather_round();
         }
