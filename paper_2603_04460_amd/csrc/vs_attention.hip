@@ -401,7 +401,6 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
             __builtin_amdgcn_s_waitcnt(0x0F70);              // the barrier publishes only what has arrived
         }
         __syncthreads();
-        bf16x8 k0[8], k1[8], vf[8], p0[2], p1[2];
         nfull = min(nfull, nstages);
         TileInfo a{false, false, nullptr, nullptr}, b = a;
         if (nfull == 0) {
@@ -416,8 +415,9 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
         };
         // one step
         // FULL: both tiles are kept whole by this row block: no tile descriptions, no masks, no tests
-        auto step = [&](int st, auto full_tag) __attribute__((always_inline)) {
-            constexpr bool FULL = decltype(full_tag)::value;
+        auto step = [&](int st, auto mode_tag) __attribute__((always_inline)) {
+            constexpr int MODE = decltype(mode_tag)::value;
+            constexpr bool FULL = MODE == 0;
             if (st > 0) {
                 __builtin_amdgcn_s_waitcnt(0x0F70);          // this wavefront's part of stage st has arrived
                 __syncthreads();
@@ -443,13 +443,54 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
                     for (int h = 0; h < 2; ++h) rows[u][h] = min(glist[32 * u + st_row + 16 * h], n - 1);
                 load_stage(rows, buf1);
             }
+            if constexpr (MODE != 2) {
+                // Both tiles live: one straight-line piece in a fixed order (the scheduling barriers keep the compiler from
+                // moving LDS reads across them: left alone it either hoists all of them, which does not fit the registers,
+                // or issues them one at a time in front of their use).  The K fragments of both tiles are read first, the
+                // two score chains are interleaved, the V fragments of both tiles are requested as soon as the K fragments
+                // are dead (they take their registers) and arrive during the softmax.
+                bf16x8 k0[8], k1[8], v0[8], v1[8], p0[2], p1[2];
+                f32x16 s0, s1, zero;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) zero[e] = 0.f;
+                read_k(2 * buf, k0);
+                read_k(2 * buf + 1, k1);
+                tiles_done += 2;
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int kk = 0; kk < 8; ++kk) {
+                    s0 = mfma32(k0[kk], qf[kk], kk == 0 ? zero : s0);
+                    s1 = mfma32(k1[kk], qf[kk], kk == 0 ? zero : s1);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                read_v(2 * buf, v0);
+                read_v(2 * buf + 1, v1);
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (!FULL) {
+                    apply_mask(s0, a, gather_tag);
+                    apply_mask(s1, b, gather_tag);
+                }
+                const float mx = fmaxf(tile_max(s0), tile_max(s1));
+                const float m_new = fmaxf(m_run, half_swap_max(mx));
+                if (__ballot((m_new - m_run) * p.c > kRescaleThreshold)) rescale(m_new);   // false when both are -inf
+                const float mc = (m_run == NEG_INF) ? 0.f : m_run * p.c;
+                float lsum = 0.f;
+                exp_part(s0, 0, 16, mc, lsum);
+                pack_p(s0, p0);
+                exp_part(s1, 0, 16, mc, lsum);
+                pack_p(s1, p1);
+                l_run += lsum;
+                pv(p0, v0);
+                pv(p1, v1);
+            } else {
             // scores of the two tiles: defined only where the tile is live (every later use is under the same test), so
             // that no registers are cleared for tiles that are skipped
+            bf16x8 k0[8], k1[8], vf[8], p0[2], p1[2];       // (local to the step: nothing is carried round the loop)
             f32x16 s0, s1, zero;
 #pragma unroll
             for (int e = 0; e < 16; ++e) zero[e] = 0.f;
             // one chain after the other; the second tile's fragments are requested before the first chain starts
-            const bool alive = FULL || a.live, blive = FULL || b.live;
+            const bool alive = a.live, blive = b.live;
             if (alive) read_k(2 * buf, k0);
             if (blive) read_k(2 * buf + 1, k1);
             if (alive) {
@@ -465,11 +506,11 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
             if (alive || blive) {
                 float mx = NEG_INF;
                 if (alive) {
-                    if constexpr (!FULL) apply_mask(s0, a, gather_tag);
+                    apply_mask(s0, a, gather_tag);
                     mx = tile_max(s0);
                 }
                 if (blive) {
-                    if constexpr (!FULL) apply_mask(s1, b, gather_tag);
+                    apply_mask(s1, b, gather_tag);
                     mx = fmaxf(mx, tile_max(s1));
                 }
                 const float m_new = fmaxf(m_run, half_swap_max(mx));
@@ -494,18 +535,29 @@ __global__ __launch_bounds__(kThreads, 2) void vs_attention_kernel(const AttnPar
                     pv(p1, vf);
                 }
             }
+            }
             a = na;
             b = nb;
             buf = buf1;
         };
         int st = 0;
-        for (; st < nfull; ++st) step(st, std::true_type{});
+        for (; st < nfull; ++st) step(st, std::integral_constant<int, 0>{});
         if (st > 0 && st < nstages) {
             stage_desc(st, d0);
             a = info(2 * st, d0[0]);
             b = info(2 * st + 1, d0[1]);
         }
-        for (; st < nstages; ++st) step(st, std::false_type{});
+        while (st < nstages) {
+            if (a.live && b.live) {
+                do {
+                    step(st, std::integral_constant<int, 1>{});
+                    ++st;
+                } while (st < nstages && a.live && b.live);
+            } else {
+                step(st, std::integral_constant<int, 2>{});
+                ++st;
+            }
+        }
         if (!(!GATHER && chain)) {
             __syncthreads();                                 // the ring and the list are reused by the next phase
             buf = 0;
