@@ -109,6 +109,8 @@ typedef struct {
     int cap_v, cap_s;
 } vs_budget_t;
 
+/* Bytes of device workspace with which vs_select_budget spreads every (head, direction) problem over many
+ * workgroups; 0 for lengths short enough for one workgroup per problem.  Contents need no initialisation. */
 size_t vs_select_budget_workspace(int heads, int64_t n);
 
 /*
@@ -116,6 +118,9 @@ size_t vs_select_budget_workspace(int heads, int64_t n);
  *   idx_v, idx_s  [heads, cap_v] / [heads, cap_s] int32 out, ascending, first cnt entries valid
  *   cnt_v, cnt_s  [heads] int32 out
  *   status        [heads] int32 out (bit-or of VS_STATUS_* over both directions) or NULL
+ *   ws, ws_bytes  device workspace of at least vs_select_budget_workspace() bytes (16-byte aligned), or NULL / 0: the
+ *                 call then uses one workgroup per problem (same results; about three times slower at 128k).  A
+ *                 non-NULL workspace that is too small is VS_ERR_WORKSPACE.
  */
 int vs_select_budget(const float* a_v, const float* a_s, int heads, int64_t n, const vs_budget_t* b,
                      int32_t* idx_v, int32_t* cnt_v, int32_t* idx_s, int32_t* cnt_s, int32_t* status,

@@ -41,7 +41,10 @@ def test_strerror_and_workspace_queries():
     assert vs.index_score_workspace(8, 131072, 1024) == 2 * 1024 * 256 * 2 + 8 * 2 * 2048 * 8 + 2 * 4 * 8 * 131072 * 4
     assert vs.index_train_workspace(8, 4096, 256) > vs.index_score_workspace(8, 4096, 256)
     assert vs.index_score_workspace(8, 131072, 100) == 0               # d_h must be a multiple of 64
-    assert vs.select_budget_workspace(8, 131072) == 0
+    # short problems need none (one workgroup each, everything in LDS); long ones: three histograms of 4096 (mass, count)
+    # per problem, the redo flags, four descent states per problem and three counts per 8192-score chunk
+    assert vs.select_budget_workspace(8, 20000) == 0
+    assert vs.select_budget_workspace(8, 131072) == 3 * 16 * 4096 * 12 + 256 + 16 * 4 * 48 + 16 * 16 * 3 * 4
 
 
 def test_host_side_argument_checks():

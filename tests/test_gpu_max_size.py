@@ -69,13 +69,16 @@ def test_indexer_and_selection_max_n(qkv):
     idx_v = torch.empty((1, cap), dtype=torch.int32, device="cuda"); idx_s = torch.empty_like(idx_v)
     cnt_v = torch.empty(1, dtype=torch.int32, device="cuda"); cnt_s = torch.empty_like(cnt_v)
     status = torch.empty(1, dtype=torch.int32, device="cuda")
-    vs.select_budget(a_v, a_s, b, idx_v, cnt_v, idx_s, cnt_s, status, None)
-    torch.cuda.synchronize()
-    for scores, idx, cnt, forced in ((a_v, idx_v, cnt_v, 4), (a_s, idx_s, cnt_s, 64)):
-        ri, rc, _, _ = oracle.select(scores.cpu().numpy(), 0, 0.9, 0, forced, cap)
-        c = int(cnt.item())
-        assert c == int(rc[0])
-        assert np.array_equal(idx[0, :c].cpu().numpy(), ri[0, :c])
+    refs = [oracle.select(scores.cpu().numpy(), 0, 0.9, 0, forced, cap) for scores, forced in ((a_v, 4), (a_s, 64))]
+    # without a workspace (one workgroup per problem) and with one (128 chunks per problem)
+    for wsel in (None, torch.empty(vs.select_budget_workspace(1, N), dtype=torch.uint8, device="cuda")):
+        idx_v.fill_(-1); idx_s.fill_(-1)
+        vs.select_budget(a_v, a_s, b, idx_v, cnt_v, idx_s, cnt_s, status, wsel)
+        torch.cuda.synchronize()
+        for (ri, rc, _, _), idx, cnt in zip(refs, (idx_v, idx_s), (cnt_v, cnt_s)):
+            c = int(cnt.item())
+            assert c == int(rc[0])
+            assert np.array_equal(idx[0, :c].cpu().numpy(), ri[0, :c])
 
 
 def test_aggregate_properties_max_n(qkv):

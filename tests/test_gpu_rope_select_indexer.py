@@ -29,7 +29,7 @@ def test_rope_matches_oracle(heads, n, pos0, theta, pairing):
 
 
 # ---------------------------------------------------------------- selection
-def _gpu_select(a_v, a_s, budget):
+def _gpu_select(a_v, a_s, budget, use_ws=True):
     heads, n = a_v.shape
     av, as_ = torch.from_numpy(a_v).cuda(), torch.from_numpy(a_s).cuda()
     idx_v = torch.full((heads, budget.cap_v), -1, dtype=torch.int32, device="cuda")
@@ -38,7 +38,8 @@ def _gpu_select(a_v, a_s, budget):
     cnt_s = torch.zeros(heads, dtype=torch.int32, device="cuda")
     status = torch.full((heads,), 99, dtype=torch.int32, device="cuda")
     nbytes = vs.select_budget_workspace(heads, n)
-    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda") if nbytes else None
+    # stale contents on purpose: the library must not rely on a clean workspace
+    ws = torch.full((nbytes,), 0xA5, dtype=torch.uint8, device="cuda") if nbytes and use_ws else None
     vs.select_budget(av, as_, budget, idx_v, cnt_v, idx_s, cnt_s, status, ws)
     torch.cuda.synchronize()
     return idx_v.cpu().numpy(), cnt_v.cpu().numpy(), idx_s.cpu().numpy(), cnt_s.cpu().numpy(), status.cpu().numpy()
@@ -113,6 +114,42 @@ def test_select_threshold_above_rounded_total():
     _check_select(a, a.copy(), vs.Budget(mode=0, tau_v=1.0, tau_s=1.0, n_sink=0, n_local=1, cap_v=n, cap_s=n))
     # and with a capacity below n: forced entries + best-ranked others, overflow flagged
     _check_select(a, a.copy(), vs.Budget(mode=0, tau_v=1.0, tau_s=1.0, n_sink=2, n_local=3, cap_v=1000, cap_s=77))
+
+
+def test_select_split_over_workgroups():
+    """Long problems with a workspace run the descent over one workgroup per 8192-score chunk: ties across chunk borders,
+    a ragged last chunk, both rules, degenerate thresholds, bad scores, the rounded-total corner and the capacity
+    overflow (redone by the single-workgroup kernel); every result equals the oracle's and the single-workgroup path's."""
+    n = 40000 + 17
+    assert vs.select_budget_workspace(2, n) > 0 and vs.select_budget_workspace(2, 20000) == 0
+    rng = np.random.default_rng(11)
+    q = (rng.integers(1, 6, size=(2, n)) / 65536.0).astype(np.float32)        # five distinct values: ties everywhere
+    u = np.full((2, n), 1.0 / n, dtype=np.float32)
+    a_v, a_s = synth.structured_scores(5, 2, n)
+    bad = a_v.copy()
+    bad[0, 5] = np.nan; bad[1, 8193] = -1.0; bad[0, 39999] = 3.0; bad[1, n - 1] = -0.0
+    sat = np.full((2, n), 2.0, dtype=np.float32)
+    sat[:, [100, 5000, n - 1]] = 2.0 ** -40
+    cases = [
+        (q, u, vs.Budget(mode=0, tau_v=0.9, tau_s=0.37, n_sink=0, n_local=1, cap_v=n, cap_s=n)),
+        (q, u, vs.Budget(mode=1, k_v=12345, k_s=n + 5, n_sink=2, n_local=3, cap_v=n, cap_s=n)),
+        (a_v, a_s, vs.Budget(mode=0, tau_v=1.0, tau_s=0.0, n_sink=4, n_local=64, cap_v=n, cap_s=n)),
+        (a_v, a_s, vs.Budget(mode=1, k_v=0, k_s=1, n_sink=4, n_local=64, cap_v=n, cap_s=n)),
+        (bad, a_s, vs.Budget(mode=0, tau_v=0.8, tau_s=0.95, n_sink=1, n_local=5000, cap_v=n, cap_s=n)),
+        (sat, sat.copy(), vs.Budget(mode=0, tau_v=1.0, tau_s=1.0, n_sink=0, n_local=1, cap_v=n, cap_s=n)),
+        (a_v, q, vs.Budget(mode=0, tau_v=0.9, tau_s=0.9, n_sink=4, n_local=64, cap_v=64, cap_s=5000)),      # overflow
+        (np.zeros((2, n), dtype=np.float32), u, vs.Budget(mode=0, tau_v=0.9, tau_s=1.0, n_sink=2, n_local=0, cap_v=n, cap_s=n)),
+    ]
+    for x_v, x_s, b in cases:
+        _check_select(x_v, x_s, b)
+        one = _gpu_select(x_v, x_s, b, use_ws=False)
+        many = _gpu_select(x_v, x_s, b, use_ws=True)
+        for r1, r2, cnt1 in ((one[0], many[0], one[1]), (one[2], many[2], one[3])):
+            for h in range(x_v.shape[0]):
+                np.testing.assert_array_equal(r1[h, :cnt1[h]], r2[h, :cnt1[h]])
+        np.testing.assert_array_equal(one[1], many[1])
+        np.testing.assert_array_equal(one[3], many[3])
+        np.testing.assert_array_equal(one[4], many[4])
 
 
 # ---------------------------------------------------------------- indexer
