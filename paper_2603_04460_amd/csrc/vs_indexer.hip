@@ -22,7 +22,10 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "vs_common.h"
+#include "vs_wave.h"
 
 namespace {
 
@@ -273,18 +276,10 @@ __global__ __launch_bounds__(kThreads) void indexer_logits_kernel(const IndexerP
                 out_s[static_cast<size_t>(head) * n + tok] = s2;
             }
             if (p.part) {
-                float mv = ok ? v : -INFINITY, ms = ok ? s2 : -INFINITY;
-#pragma unroll
-                for (int d = 32; d >= 1; d >>= 1) {
-                    mv = fmaxf(mv, __shfl_xor(mv, d));
-                    ms = fmaxf(ms, __shfl_xor(ms, d));
-                }
-                float ev = ok ? expf(v - mv) : 0.f, es = ok ? expf(s2 - ms) : 0.f;
-#pragma unroll
-                for (int d = 32; d >= 1; d >>= 1) {
-                    ev += __shfl_xor(ev, d);
-                    es += __shfl_xor(es, d);
-                }
+                // (this stretch delays the two wavefronts that run it, and through the tile's barrier all eight: the
+                // reductions stay on the vector ALU)
+                const float mv = wave_max(ok ? v : -INFINITY), ms = wave_max(ok ? s2 : -INFINITY);
+                const float ev = wave_sum(ok ? expf(v - mv) : 0.f), es = wave_sum(ok ? expf(s2 - ms) : 0.f);
                 const int pt = (kTokTile / 64) * tile_in_head + wave;           // statistics per 64 tokens
                 if (lane == 0 && pt < p.parts_per_head) {
                     p.part[(static_cast<size_t>(head) * 2 + 0) * p.parts_per_head + pt] = make_float2(mv, ev);
