@@ -72,6 +72,10 @@ def test_host_side_argument_checks():
     assert L.vs_select_budget(vp(p), vp(p), 1, 64, ctypes.byref(b), vp(p), vp(p), vp(p), vp(p), None, None, 0, None) == -4
     b = binding._Budget(2, 0.5, 0.5, 0, 0, 0, 1, 8, 8)
     assert L.vs_select_budget(vp(p), vp(p), 1, 64, ctypes.byref(b), vp(p), vp(p), vp(p), vp(p), None, None, 0, None) == -1
+    # long problem with a workspace that is too small / misaligned: refused on the host, before any launch
+    b = binding._Budget(0, 0.5, 0.5, 0, 0, 0, 1, 8, 8)
+    assert L.vs_select_budget(vp(p), vp(p), 1, 65536, ctypes.byref(b), vp(p), vp(p), vp(p), vp(p), None, vp(p), 1024, None) == -3
+    assert L.vs_select_budget(vp(p), vp(p), 1, 65536, ctypes.byref(b), vp(p), vp(p), vp(p), vp(p), None, vp(p + 4), 1 << 24, None) == -1
     w = binding._Indexer(p, p, p, p, 0.0, 0.0, 100, 1)
     assert L.vs_index_score(vp(p), vp(p), 1, 64, ctypes.byref(w), vp(p), vp(p), vp(p), 1 << 20, None) == -2
     w = binding._Indexer(p, p, p, p, 0.0, 0.0, 256, 7)

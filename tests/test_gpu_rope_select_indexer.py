@@ -144,6 +144,9 @@ def test_select_split_over_workgroups():
         _check_select(x_v, x_s, b)
         one = _gpu_select(x_v, x_s, b, use_ws=False)
         many = _gpu_select(x_v, x_s, b, use_ws=True)
+        again = _gpu_select(x_v, x_s, b, use_ws=True)           # integer atomics: the same bits whatever the order
+        for r1, r2 in zip(many, again):
+            np.testing.assert_array_equal(r1, r2)
         for r1, r2, cnt1 in ((one[0], many[0], one[1]), (one[2], many[2], one[3])):
             for h in range(x_v.shape[0]):
                 np.testing.assert_array_equal(r1[h, :cnt1[h]], r2[h, :cnt1[h]])
