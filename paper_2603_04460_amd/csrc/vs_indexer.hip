@@ -23,6 +23,7 @@
 #include <stdint.h>
 
 #include <type_traits>
+#include <utility>
 
 #include "vs_common.h"
 #include "vs_wave.h"
@@ -94,10 +95,16 @@ __device__ __forceinline__ float gelu_logistic(float x) {
     return x * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(x * p));
 }
 
-template <int ACT>
-__device__ __forceinline__ float activate(float x) {
-    if (ACT == 0) return x * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
-    return gelu_logistic(x);
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): a loop whose counter is a constant in every iteration
+// by construction (an unrolling pragma is a request; when it is not honoured, register arrays indexed by the counter go
+// to scratch memory)
+template <int... I, typename F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F&&>(f));
 }
 
 struct IndexerParams {
@@ -195,60 +202,163 @@ __global__ __launch_bounds__(kThreads) void indexer_logits_kernel(const IndexerP
             // Block j: tokens 32 j + col.  The accumulator starts from the bias; lane (token col, hh) holds hidden units
             // 32 wave + 8 a + 4 hh + c.  X^T fragments (B operand: lane = token column, features 16 kk + 8 hh .. + 7) come from
             // LDS a few steps ahead of the products that use them.
-            constexpr int kLook = 4;
-            auto mfma_block = [&](int j, f32x16& acc) __attribute__((always_inline)) {
-#pragma unroll
-                for (int a = 0; a < 4; ++a) {
-                    const float4 bu = *reinterpret_cast<const float4*>(sbU + 32 * wave + 8 * a + 4 * hh);
-                    acc[4 * a] = bu.x;
-                    acc[4 * a + 1] = bu.y;
-                    acc[4 * a + 2] = bu.z;
-                    acc[4 * a + 3] = bu.w;
-                }
+            //
+            // fused(jn, accn, j, accc): the 32 matrix instructions of block jn, each followed by a piece of the activation
+            // of block j, written out in issue order with scheduling barriers between the pieces.  A wavefront issues in
+            // order and a matrix instruction waits at issue until the matrix core takes it (32 clocks apart), so vector
+            // work that follows a run of matrix instructions in the program starts only when the run is through; both
+            // wavefronts of a SIMD belong to this workgroup and meet at the tile's barrier, so they do not cover for each
+            // other either.  (The declarative form, scheduling-group barriers, left the matrix instructions in one run.)
+            // The activation of a block is cut into stages of four independent elements (one group), so that no
+            // instruction waits for its predecessor; pure arithmetic is pinned with empty asm statements, or the
+            // compiler moves it to its use.
+            constexpr int kLook = 2;
+            constexpr int kStages = 7;                       // stages of one group's activation (SiLU)
+            constexpr int kGrp = 4;                          // elements per group
+            constexpr int kPieces = (16 / kGrp) * kStages;
+            auto fused = [&](int jn, f32x16& accn, int j, const f32x16& accc, auto mfma_tag, auto act_tag) __attribute__((always_inline)) {
+                constexpr bool MFMA = decltype(mfma_tag)::value, ACTV = decltype(act_tag)::value;
                 uint4 xq[kLook];
                 auto xread = [&](int kk) __attribute__((always_inline)) -> uint4 {
-                    return *reinterpret_cast<const uint4*>(xt + (32 * j + col) * kXPitch + (((2 * kk + hh) << 4) ^ sw16));
+                    return *reinterpret_cast<const uint4*>(xt + (32 * jn + col) * kXPitch + (((2 * kk + hh) << 4) ^ sw16));
                 };
+                if constexpr (MFMA) {
 #pragma unroll
-                for (int kk = 0; kk < kLook; ++kk) xq[kk] = xread(kk);
+                    for (int a = 0; a < 4; ++a) {
+                        const float4 bu = *reinterpret_cast<const float4*>(sbU + 32 * wave + 8 * a + 4 * hh);
+                        accn[4 * a] = bu.x;
+                        accn[4 * a + 1] = bu.y;
+                        accn[4 * a + 2] = bu.z;
+                        accn[4 * a + 3] = bu.w;
+                    }
 #pragma unroll
-                for (int kk = 0; kk < 16; ++kk) {
-                    const bf16x8 xb = __builtin_bit_cast(bf16x8, xq[kk % kLook]);
-                    if (kk + kLook < 16) xq[kk % kLook] = xread(kk + kLook);
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(whi[kk], xb, acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wlo[kk], xb, acc, 0, 0, 0);
+                    for (int kk = 0; kk < kLook; ++kk) xq[kk] = xread(kk);
+                }
+                float t[kGrp], lvp[kGrp], lsp[kGrp];
+#pragma unroll
+                for (int c = 0; c < kGrp; ++c) lvp[c] = lsp[c] = 0.f;
+                float wv_[kGrp], ws_[kGrp];
+                // piece pc: stage pc % kStages of group g = pc / kStages: accumulator elements 4 g + c, hidden units 32 wave + 8 g + 4 hh + c;
+                // the two logit sums are kept per element slot c (no chain of dependent additions) and added at the end
+                auto piece = [&](auto pc_tag) __attribute__((always_inline)) {
+                    constexpr int pc = decltype(pc_tag)::value;
+                    constexpr int g = pc / kStages, st = pc % kStages;
+                    if (st == 0) {
+                        const int u = 32 * wave + 8 * ((kGrp * g) >> 2) + 4 * hh + ((kGrp * g) & 3);
+#pragma unroll
+                        for (int c = 0; c < kGrp; ++c) {
+                            wv_[c] = sWV[u + c];
+                            ws_[c] = sWS[u + c];
+                        }
+                    }
+#pragma unroll
+                    for (int c = 0; c < kGrp; ++c) {
+                        const float x = accc[kGrp * g + c];
+                        constexpr float kL = -1.4426950408889634f;
+                        // SiLU: x / (1 + 2^(-log2(e) x))
+                        if (st == 0) t[c] = kL * x;
+                        if (st == 1) t[c] = __builtin_amdgcn_exp2f(t[c]);
+                        if (st == 2) t[c] = 1.f + t[c];
+                        if (st == 3) t[c] = __builtin_amdgcn_rcpf(t[c]);
+                        if (st == 4) t[c] = x * t[c];
+                        if (st == 5) lvp[c] = fmaf(t[c], wv_[c], lvp[c]);
+                        if (st == 6) lsp[c] = fmaf(t[c], ws_[c], lsp[c]);
+                        if (st < kStages - 2) asm volatile("" : "+v"(t[c]));
+                        else if (st == kStages - 2) asm volatile("" : "+v"(lvp[c]));
+                        else asm volatile("" : "+v"(lsp[c]));
+                    }
+                };
+                static_for<32>([&](auto i_tag) __attribute__((always_inline)) {
+                    constexpr int i = decltype(i_tag)::value;
+                    if constexpr (MFMA) {
+                        constexpr int kk = i >> 1;
+                        const bf16x8 xb = __builtin_bit_cast(bf16x8, xq[kk % kLook]);
+                        accn = __builtin_amdgcn_mfma_f32_32x32x16_bf16((i & 1) ? wlo[kk] : whi[kk], xb, accn, 0, 0, 0);
+                        if constexpr ((i & 1) && kk + kLook < 16) xq[kk % kLook] = xread(kk + kLook);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if constexpr (ACTV) {
+                        // pieces [i kPieces / 32, (i + 1) kPieces / 32)
+                        constexpr int lo = (i * kPieces) / 32, hi = ((i + 1) * kPieces) / 32;
+                        static_for<hi - lo>([&](auto q_tag) __attribute__((always_inline)) {
+                            piece(std::integral_constant<int, lo + decltype(q_tag)::value>{});
+                        });
+                        if constexpr (MFMA) __builtin_amdgcn_sched_barrier(0);
+                    }
+                });
+                if constexpr (ACTV) {
+                    // both halves of the wavefront hold the same sums afterwards and write the same value
+                    float lv = 0.f, ls = 0.f;
+#pragma unroll
+                    for (int c = 0; c < kGrp; ++c) {
+                        lv += lvp[c];
+                        ls += lsp[c];
+                    }
+                    red[(par * kWaves + wave) * kTokTile + 32 * j + col] = make_float2(half_swap_sum(lv), half_swap_sum(ls));
                 }
             };
-            auto act_block = [&](int j, const f32x16& acc) __attribute__((always_inline)) {
-                float lv = 0.f, ls = 0.f;
+            if constexpr (ACT == 0) {
+                using T = std::true_type;
+                using F = std::false_type;
+                f32x16 acc[2];
+                fused(0, acc[0], 0, acc[0], T{}, F{});
 #pragma unroll
-                for (int a = 0; a < 4; ++a) {
-                    const float4 wv = *reinterpret_cast<const float4*>(sWV + 32 * wave + 8 * a + 4 * hh);
-                    const float4 ws = *reinterpret_cast<const float4*>(sWS + 32 * wave + 8 * a + 4 * hh);
-                    const float wv_[4] = {wv.x, wv.y, wv.z, wv.w}, ws_[4] = {ws.x, ws.y, ws.z, ws.w};
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        const float z = activate<ACT>(acc[4 * a + c]);
-                        lv = fmaf(z, wv_[c], lv);
-                        ls = fmaf(z, ws_[c], ls);
-                    }
+                for (int j = 0; j < kBlocks; ++j) {
+                    if (j + 1 < kBlocks) fused(j + 1, acc[(j + 1) & 1], j, acc[j & 1], T{}, T{});
+                    else fused(0, acc[0], j, acc[j & 1], F{}, T{});
                 }
-                // both halves of the wavefront hold the same sums afterwards and write the same value
-                red[(par * kWaves + wave) * kTokTile + 32 * j + col] = make_float2(half_swap_sum(lv), half_swap_sum(ls));
-            };
-            f32x16 acc[2];
-            mfma_block(0, acc[0]);
+            } else {
+                // GELU: its vector work (84 clocks per element against 59 for SiLU) outweighs the matrix work of a block, the
+                // kernel runs at the vector pipe's pace either way, and the fixed order above only takes freedom from the
+                // compiler (measured 5 % slower): blocks as plain code, matrix products of block j + 1 before the activation
+                // of block j.
+                auto mfma_block = [&](int j, f32x16& acc) __attribute__((always_inline)) {
 #pragma unroll
-            for (int j = 0; j < kBlocks; ++j) {
-                if (j + 1 < kBlocks) mfma_block(j + 1, acc[(j + 1) & 1]);
-                act_block(j, acc[j & 1]);
-                if (j + 1 < kBlocks) {
-                    // issue order of this stretch: one matrix instruction, then a few vector instructions, 32 times
-#pragma unroll
-                    for (int i = 0; i < 32; ++i) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x002, ACT == 0 ? 4 : 6, 0);
+                    for (int a = 0; a < 4; ++a) {
+                        const float4 bu = *reinterpret_cast<const float4*>(sbU + 32 * wave + 8 * a + 4 * hh);
+                        acc[4 * a] = bu.x;
+                        acc[4 * a + 1] = bu.y;
+                        acc[4 * a + 2] = bu.z;
+                        acc[4 * a + 3] = bu.w;
                     }
+                    constexpr int kAhead = 4;
+                    uint4 xq[kAhead];
+                    auto xread = [&](int kk) __attribute__((always_inline)) -> uint4 {
+                        return *reinterpret_cast<const uint4*>(xt + (32 * j + col) * kXPitch + (((2 * kk + hh) << 4) ^ sw16));
+                    };
+#pragma unroll
+                    for (int kk = 0; kk < kAhead; ++kk) xq[kk] = xread(kk);
+#pragma unroll
+                    for (int kk = 0; kk < 16; ++kk) {
+                        const bf16x8 xb = __builtin_bit_cast(bf16x8, xq[kk % kAhead]);
+                        if (kk + kAhead < 16) xq[kk % kAhead] = xread(kk + kAhead);
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(whi[kk], xb, acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wlo[kk], xb, acc, 0, 0, 0);
+                    }
+                };
+                auto act_block = [&](int j, const f32x16& acc) __attribute__((always_inline)) {
+                    float lv = 0.f, ls = 0.f;
+#pragma unroll
+                    for (int a = 0; a < 4; ++a) {
+                        const float4 wv = *reinterpret_cast<const float4*>(sWV + 32 * wave + 8 * a + 4 * hh);
+                        const float4 ws = *reinterpret_cast<const float4*>(sWS + 32 * wave + 8 * a + 4 * hh);
+                        const float wv_[4] = {wv.x, wv.y, wv.z, wv.w}, ws_[4] = {ws.x, ws.y, ws.z, ws.w};
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            const float z = gelu_logistic(acc[4 * a + c]);
+                            lv = fmaf(z, wv_[c], lv);
+                            ls = fmaf(z, ws_[c], ls);
+                        }
+                    }
+                    // both halves of the wavefront hold the same sums afterwards and write the same value
+                    red[(par * kWaves + wave) * kTokTile + 32 * j + col] = make_float2(half_swap_sum(lv), half_swap_sum(ls));
+                };
+                f32x16 acc[2];
+                mfma_block(0, acc[0]);
+#pragma unroll
+                for (int j = 0; j < kBlocks; ++j) {
+                    if (j + 1 < kBlocks) mfma_block(j + 1, acc[(j + 1) & 1]);
+                    act_block(j, acc[j & 1]);
                 }
             }
         }
